@@ -1,0 +1,156 @@
+/*
+ * gcn355 — full-batch Kipf-Welling GCN training step on one partition subgraph, for MI355X (gfx950).
+ *
+ * The unit of work is what one worker of the paper's data-parallel scheme does in one epoch
+ * (Section 3.2): it holds a complete copy of the network and trains it, full batch, on its own
+ * partition, which has already been extended by a few percent of vertices that approximate the
+ * other partitions (Section 3.1, Algorithm 1).  To this library those extra vertices are ordinary
+ * rows of the same adjacency and feature matrix; they are simply outside the train mask.
+ *
+ * Model (Section 4.1): H^l = sigma(A_hat H^{l-1} W^l), H^0 = X, with X holding one feature row
+ * per vertex and A the adjacency matrix (Section 2.1).  A_hat, the "normalized adjacency matrix"
+ * of the footnote to Section 4.1, is D^-1/2 (A + I) D^-1/2, D = row sums of A + I, A binary.
+ * sigma is ReLU on hidden layers; the last layer's output are the logits.  The loss is the
+ * softmax cross-entropy averaged over the vertices of the train mask; accuracy (the micro-F1 of
+ * Section 2.2, which equals plain accuracy for one label per vertex) is measured on the same mask.
+ * No bias terms.  The update is plain SGD.
+ *
+ * Conventions for every call
+ *   - Pointers marked [dev] are device pointers valid on the current HIP device; [host] are host
+ *     pointers.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The library allocates no device memory: the caller hands over workspaces (sized by the
+ *     *_workspace_bytes calls, 256-byte aligned) and keeps them alive until the matching destroy.
+ *     Everything else passed to a create call is copied and may be released once it returns.
+ *   - Dense matrices crossing this boundary are row-major, float32, without padding.
+ *   - Return value: GCN_OK (0) or a negative gcn_status.  No call aborts or throws; after a
+ *     failure gcn_last_error() returns a thread-local description.  A failed create leaves *out
+ *     NULL.  Calls on one model must not overlap in time (one stream at a time).
+ */
+#ifndef GCN355_H
+#define GCN355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gcn_graph gcn_graph;
+typedef struct gcn_model gcn_model;
+
+enum gcn_status {
+    GCN_OK = 0,
+    GCN_EINVAL = -1,     /* null pointer, bad size, call out of order, empty train mask        */
+    GCN_EGRAPH = -2,     /* rowptr not monotone / wrong ends, column out of range, not symmetric */
+    GCN_ELABEL = -3,     /* a label outside [0, n_classes)                                     */
+    GCN_EWORKSPACE = -4, /* workspace missing, misaligned or too small                         */
+    GCN_EHIP = -5        /* a HIP runtime call failed (text in gcn_last_error)                  */
+};
+
+/* Storage type of features and activations.  Weights, gradients of weights, the loss and every
+ * accumulator are float32 in both modes. */
+enum gcn_dtype { GCN_F32 = 0, GCN_BF16 = 1 };
+
+/* Tensors readable with gcn_get_tensor; `layer` counts from 1. */
+enum gcn_tensor {
+    GCN_T_W = 0,      /* W^l                      d_{l-1} x d_l                                  */
+    GCN_T_DW = 1,     /* dLoss/dW^l               d_{l-1} x d_l   (after gcn_backward)           */
+    GCN_T_H = 2,      /* H^l, l < L               n x d_l         (after gcn_forward)            */
+    GCN_T_LOGITS = 3, /* A_hat H^{L-1} W^L        n x d_L         (layer argument ignored)       */
+    GCN_T_G = 4,      /* A_hat (dLoss/dZ^l)       n x d_l         (after gcn_backward)           */
+    GCN_T_DZ = 5      /* dLoss/dZ^l, Z^l = A_hat H^{l-1} W^l      n x d_l (after gcn_backward)   */
+};
+
+const char *gcn_last_error(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Graph: the partition's adjacency, features, labels and train mask (inputs of Section 2.1/2.2).
+ *
+ * gcn_graph_create takes the raw adjacency A in CSR form: rowptr [dev, n+1, int64, rowptr[0] = 0,
+ * rowptr[n] = nnz_in], col [dev, nnz_in, int32].  Column order inside a row is free, repeated
+ * entries and explicit self-loops are allowed; the pattern must be symmetric.  On the GPU it builds
+ * the canonical pattern of A + I (columns ascending, distinct, exactly one self-loop per row), the
+ * integer degrees d_i = row length, d_i^-1/2, and the row schedule of the aggregation kernels.
+ * feat [dev, n x f float32], labels [dev, n, int32 in [0, n_classes)], train_mask [dev, n, uint8,
+ * non-zero = in the mask].  store_dtype selects how the library keeps its own copy of X.
+ * The call is synchronous (it reads back sizes and error flags).  Errors: GCN_EGRAPH, GCN_ELABEL,
+ * GCN_EINVAL (empty mask, n <= 0 ...), GCN_EWORKSPACE.
+ */
+int gcn_graph_workspace_bytes(int64_t n, int64_t nnz_in, int32_t f, int store_dtype, size_t *bytes);
+int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col,
+                     const float *feat, int32_t f, int store_dtype, const int32_t *labels,
+                     const uint8_t *train_mask, int32_t n_classes, void *workspace, size_t workspace_bytes,
+                     void *stream);
+int gcn_graph_destroy(gcn_graph *g);
+
+/* Sizes: n, E = nonzeros of A + I, size of the train mask, largest degree.  Any pointer may be NULL. */
+int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_train, int32_t *max_degree);
+
+/* Copies the canonical arrays to caller buffers [dev]: rowptr (n+1 int64), col (E int32), deg (n int32),
+ * dinv (n float32).  Any pointer may be NULL.  Asynchronous on `stream`. */
+int gcn_graph_get_csr(const gcn_graph *g, int64_t *rowptr, int32_t *col, int32_t *deg, float *dinv, void *stream);
+
+/* out = A_hat in, for a caller matrix [dev, n x width float32] (the aggregation of Section 4.1's layer
+ * rule on its own; cost term nnz(A) F of Section 5.4).  `workspace` [dev] of at least
+ * gcn_aggregate_workspace_bytes.  Asynchronous. */
+int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, size_t *bytes);
+int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Model: L layers of widths dims[0..L] (dims[0] = f, dims[L] = n_classes), one local copy of the
+ * network as each worker holds it (Section 3.2).  dropout_p in [0, 1) applies to hidden activations
+ * in training mode only; the keep mask is the integer function
+ *     keep(e) = [ (mix(key + e * 0x9E3779B97F4A7C15) >> 32) >= floor(p * 2^32) ],
+ *     key = mix(mix(seed) ^ epoch * 0xD1B54A32D192ED03 ^ layer * 0x8CB92BA72F3D8DD7),
+ * mix = the SplitMix64 output function, e = row * d_l + column, epoch = number of gcn_sgd_step
+ * calls so far.  Weights start at zero; set them with gcn_set_weights.
+ */
+int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes);
+int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype,
+                     float dropout_p, uint64_t seed, void *workspace, size_t workspace_bytes, void *stream);
+int gcn_model_destroy(gcn_model *m);
+
+/* flat = W^1 | W^2 | ... each d_{l-1} x d_l row-major float32; [host] if on_host else [dev].  Synchronous
+ * when on_host. */
+int gcn_set_weights(gcn_model *m, const float *flat, int on_host, void *stream);
+
+/* Copies one tensor, unpadded row-major float32, into dst [dev, dst_floats >= rows*cols].  Asynchronous. */
+int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_floats, void *stream);
+
+/* Forward pass of Section 4.1's rule over all layers: for l = 1..L, Z^l = A_hat (H^{l-1} W^l),
+ * H^l = relu(Z^l) (times the dropout mask / (1-p) if training != 0 and p > 0).  Asynchronous. */
+int gcn_forward(gcn_model *m, int training, void *stream);
+
+/* Masked softmax cross-entropy (mean over the train mask) and accuracy (fraction of masked vertices
+ * whose arg-max logit, lowest index on ties, equals the label — the micro-F1 of Section 2.2).  Also
+ * stages dLoss/dlogits for gcn_backward.  Needs gcn_forward first.  If loss and acc [host] are both
+ * NULL the call only enqueues work; otherwise it waits for the stream and writes them. */
+int gcn_loss_acc(gcn_model *m, float *loss, float *acc, void *stream);
+
+/* The integers behind the accuracy of the last gcn_loss_acc: how many masked vertices were classified
+ * correctly, and the size of the mask.  Waits for the stream.  Either pointer [host] may be NULL. */
+int gcn_loss_acc_counts(gcn_model *m, int64_t *correct, int64_t *n_train, void *stream);
+
+/* Backward pass: for l = L..1, G = A_hat dZ^l (A_hat is symmetric, so the same pattern serves),
+ * dW^l = H^{l-1}^T G, dZ^{l-1} = (G W^l^T) * [Z^{l-1} > 0] (* dropout mask / (1-p)).  Needs gcn_forward and
+ * gcn_loss_acc first (GCN_EINVAL otherwise).  Asynchronous. */
+int gcn_backward(gcn_model *m, void *stream);
+
+/* W^l <- W^l - lr dW^l for all layers; advances the epoch counter.  Needs gcn_backward.  Asynchronous. */
+int gcn_sgd_step(gcn_model *m, float lr, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Kernel timing for benchmarks: when enabled, every aggregation (SpMM) launch of the calls above is
+ * bracketed by HIP events on the launch stream.  gcn_timing_read waits for the events and returns,
+ * for launches of the given width since the last reset, their count and total milliseconds.
+ */
+int gcn_timing_enable(int on);
+int gcn_timing_reset(void);
+int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCN355_H */

@@ -1,0 +1,248 @@
+"""Thin ctypes binding of libgcn355.so: argument marshalling only.
+
+Every step of the training path runs in the library's HIP kernels.  PyTorch supplies
+device memory (tensors own the workspaces) and the stream.  There is no CPU fallback:
+if the library has not been built, importing this module's `lib()` raises.
+The Python functions carry the same names as the C entry points in include/gcn355.h.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgcn355.so")
+
+GCN_F32, GCN_BF16 = 0, 1
+GCN_T_W, GCN_T_DW, GCN_T_H, GCN_T_LOGITS, GCN_T_G, GCN_T_DZ = 0, 1, 2, 3, 4, 5
+
+STATUS = {0: "GCN_OK", -1: "GCN_EINVAL", -2: "GCN_EGRAPH", -3: "GCN_ELABEL", -4: "GCN_EWORKSPACE", -5: "GCN_EHIP"}
+
+EXPORTS = [
+    "gcn_last_error", "gcn_graph_workspace_bytes", "gcn_graph_create", "gcn_graph_destroy", "gcn_graph_info",
+    "gcn_graph_get_csr", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
+    "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
+    "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
+]
+
+_lib = None
+
+
+class GcnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("%s (%d): %s" % (STATUS.get(code, "?"), code, text))
+        self.code = code
+
+
+def lib():
+    """Load the shared library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libgcn355.so is missing at %s: build it with "
+                              "`python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(or python paper_2012_04930_amd/build.py)" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_size_t
+        L.gcn_last_error.restype = C.c_char_p
+        L.gcn_last_error.argtypes = []
+        L.gcn_graph_workspace_bytes.argtypes = [i64, i64, i32, C.c_int, C.POINTER(sz)]
+        L.gcn_graph_create.argtypes = [C.POINTER(vp), i64, i64, vp, vp, vp, i32, C.c_int, vp, vp, i32, vp, sz, vp]
+        L.gcn_graph_destroy.argtypes = [vp]
+        L.gcn_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
+        L.gcn_graph_get_csr.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.gcn_aggregate_workspace_bytes.argtypes = [vp, i32, C.c_int, C.POINTER(sz)]
+        L.gcn_aggregate.argtypes = [vp, vp, vp, i32, C.c_int, vp, sz, vp]
+        L.gcn_model_workspace_bytes.argtypes = [vp, i32, C.POINTER(i32), C.c_int, C.POINTER(sz)]
+        L.gcn_model_create.argtypes = [C.POINTER(vp), vp, i32, C.POINTER(i32), C.c_int, C.c_float, C.c_uint64, vp, sz,
+                                       vp]
+        L.gcn_model_destroy.argtypes = [vp]
+        L.gcn_set_weights.argtypes = [vp, vp, C.c_int, vp]
+        L.gcn_get_tensor.argtypes = [vp, C.c_int, C.c_int, vp, sz, vp]
+        L.gcn_forward.argtypes = [vp, C.c_int, vp]
+        L.gcn_loss_acc.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
+        L.gcn_loss_acc_counts.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), vp]
+        L.gcn_backward.argtypes = [vp, vp]
+        L.gcn_sgd_step.argtypes = [vp, C.c_float, vp]
+        L.gcn_timing_enable.argtypes = [C.c_int]
+        L.gcn_timing_reset.argtypes = []
+        L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
+        for name in EXPORTS:
+            if name != "gcn_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise GcnError(rc, lib().gcn_last_error().decode("utf-8", "replace"))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype) -> int:
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, (t.device, t.dtype, dtype)
+    return t.data_ptr()
+
+
+def _workspace(nbytes: int) -> torch.Tensor:
+    # torch's caching allocator returns 512-byte aligned blocks
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    assert ws.data_ptr() % 256 == 0
+    return ws
+
+
+class Graph:
+    """Owns the graph handle and the torch tensor that backs its workspace."""
+
+    def __init__(self, handle, ws, n, f, n_classes):
+        self.handle, self.ws, self.n, self.f, self.n_classes = handle, ws, n, f, n_classes
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().gcn_graph_destroy(self.handle)
+            self.handle = None
+
+
+def gcn_graph_create(rowptr: torch.Tensor, col: torch.Tensor, feat: torch.Tensor, labels: torch.Tensor,
+                     train_mask: torch.Tensor, n_classes: int, store_dtype: int = GCN_F32) -> Graph:
+    L = lib()
+    n = rowptr.numel() - 1
+    nnz = col.numel()
+    f = feat.shape[1]
+    need = C.c_size_t()
+    _check(L.gcn_graph_workspace_bytes(n, nnz, f, store_dtype, C.byref(need)))
+    ws = _workspace(need.value)
+    h = C.c_void_p()
+    _check(L.gcn_graph_create(C.byref(h), n, nnz, _dev(rowptr, torch.int64), _dev(col, torch.int32) if nnz else None,
+                              _dev(feat, torch.float32), f, store_dtype, _dev(labels, torch.int32),
+                              _dev(train_mask, torch.uint8), n_classes, ws.data_ptr(), ws.numel(), _stream()))
+    return Graph(h, ws, n, f, n_classes)
+
+
+def gcn_graph_info(g: Graph) -> dict:
+    n, nnz, nt, md = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int32()
+    _check(lib().gcn_graph_info(g.handle, C.byref(n), C.byref(nnz), C.byref(nt), C.byref(md)))
+    return {"n": n.value, "nnz": nnz.value, "n_train": nt.value, "max_degree": md.value}
+
+
+def gcn_graph_get_csr(g: Graph):
+    info = gcn_graph_info(g)
+    rowptr = torch.empty(info["n"] + 1, dtype=torch.int64, device="cuda")
+    col = torch.empty(info["nnz"], dtype=torch.int32, device="cuda")
+    deg = torch.empty(info["n"], dtype=torch.int32, device="cuda")
+    dinv = torch.empty(info["n"], dtype=torch.float32, device="cuda")
+    _check(lib().gcn_graph_get_csr(g.handle, rowptr.data_ptr(), col.data_ptr(), deg.data_ptr(), dinv.data_ptr(),
+                                   _stream()))
+    return rowptr, col, deg, dinv
+
+
+def gcn_aggregate(g: Graph, x: torch.Tensor, dtype: int = GCN_F32, ws: torch.Tensor | None = None) -> torch.Tensor:
+    L = lib()
+    assert x.shape[0] == g.n
+    width = x.shape[1]
+    need = C.c_size_t()
+    _check(L.gcn_aggregate_workspace_bytes(g.handle, width, dtype, C.byref(need)))
+    if ws is None:
+        ws = _workspace(need.value)
+    out = torch.empty_like(x)
+    _check(L.gcn_aggregate(g.handle, _dev(x, torch.float32), out.data_ptr(), width, dtype, ws.data_ptr(), ws.numel(),
+                           _stream()))
+    return out
+
+
+class Model:
+    def __init__(self, handle, ws, graph, dims):
+        self.handle, self.ws, self.graph, self.dims = handle, ws, graph, list(dims)
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().gcn_model_destroy(self.handle)
+            self.handle = None
+
+
+def gcn_model_create(g: Graph, dims, dtype: int = GCN_F32, dropout_p: float = 0.0, seed: int = 0) -> Model:
+    L = lib()
+    nl = len(dims) - 1
+    arr = (C.c_int32 * (nl + 1))(*dims)
+    need = C.c_size_t()
+    _check(L.gcn_model_workspace_bytes(g.handle, nl, arr, dtype, C.byref(need)))
+    ws = _workspace(need.value)
+    h = C.c_void_p()
+    _check(L.gcn_model_create(C.byref(h), g.handle, nl, arr, dtype, dropout_p, seed, ws.data_ptr(), ws.numel(),
+                              _stream()))
+    return Model(h, ws, g, dims)
+
+
+def gcn_set_weights(m: Model, weights) -> None:
+    """weights: list of [d_in, d_out] float32 arrays/tensors, or one flat tensor."""
+    if isinstance(weights, (list, tuple)):
+        flat = np.concatenate([np.asarray(w, dtype=np.float32).reshape(-1) for w in weights])
+    else:
+        flat = weights
+    if isinstance(flat, torch.Tensor) and flat.is_cuda:
+        _check(lib().gcn_set_weights(m.handle, _dev(flat, torch.float32), 0, _stream()))
+    else:
+        flat = np.ascontiguousarray(np.asarray(flat, dtype=np.float32))
+        _check(lib().gcn_set_weights(m.handle, flat.ctypes.data, 1, _stream()))
+
+
+def gcn_get_tensor(m: Model, which: int, layer: int = 0) -> torch.Tensor:
+    n = m.graph.n
+    if which == GCN_T_LOGITS:
+        layer = len(m.dims) - 1
+    rows = m.dims[layer - 1] if which in (GCN_T_W, GCN_T_DW) else n
+    cols = m.dims[layer]
+    out = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    _check(lib().gcn_get_tensor(m.handle, which, layer, out.data_ptr(), out.numel(), _stream()))
+    return out
+
+
+def gcn_forward(m: Model, training: bool = True) -> None:
+    _check(lib().gcn_forward(m.handle, 1 if training else 0, _stream()))
+
+
+def gcn_loss_acc(m: Model, sync: bool = True):
+    """-> (loss, accuracy) as Python floats, or None when sync is False (work is only enqueued)."""
+    if not sync:
+        _check(lib().gcn_loss_acc(m.handle, None, None, _stream()))
+        return None
+    loss, acc = C.c_float(), C.c_float()
+    _check(lib().gcn_loss_acc(m.handle, C.byref(loss), C.byref(acc), _stream()))
+    return loss.value, acc.value
+
+
+def gcn_loss_acc_counts(m: Model):
+    """-> (correct, n_train) integers of the last gcn_loss_acc."""
+    c, n = C.c_int64(), C.c_int64()
+    _check(lib().gcn_loss_acc_counts(m.handle, C.byref(c), C.byref(n), _stream()))
+    return c.value, n.value
+
+
+def gcn_backward(m: Model) -> None:
+    _check(lib().gcn_backward(m.handle, _stream()))
+
+
+def gcn_sgd_step(m: Model, lr: float) -> None:
+    _check(lib().gcn_sgd_step(m.handle, lr, _stream()))
+
+
+def gcn_timing_enable(on: bool) -> None:
+    _check(lib().gcn_timing_enable(1 if on else 0))
+
+
+def gcn_timing_reset() -> None:
+    _check(lib().gcn_timing_reset())
+
+
+def gcn_timing_read(width: int):
+    """-> (launches, total milliseconds) of aggregation launches of this width since the last reset."""
+    cnt, ms = C.c_int64(), C.c_double()
+    _check(lib().gcn_timing_read(width, C.byref(cnt), C.byref(ms)))
+    return cnt.value, ms.value

@@ -1,0 +1,644 @@
+// C ABI of libgcn355.so and the host-side step scheduler: which kernel runs when, on which buffer.
+// The arithmetic lives in the kernels; this file only validates arguments, carves the caller's
+// workspaces and enqueues launches (layer rule and training scheme: Sections 4.1 and 3.2).
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "common.hpp"
+
+namespace gcn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+// ------------------------------------------------------------------------------------------- timing
+namespace {
+struct TimedLaunch {
+    int width;
+    hipEvent_t start, stop;
+};
+std::mutex g_tmutex;
+bool g_timing = false;
+std::vector<TimedLaunch> g_launches;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_free_events;
+hipEvent_t g_open_stop = nullptr;
+}  // namespace
+
+void timing_begin(int width, hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    g_open_stop = nullptr;
+    if (!g_timing) return;
+    std::pair<hipEvent_t, hipEvent_t> ev;
+    if (!g_free_events.empty()) {
+        ev = g_free_events.back();
+        g_free_events.pop_back();
+    } else {
+        if (hipEventCreate(&ev.first) != hipSuccess) return;
+        if (hipEventCreate(&ev.second) != hipSuccess) {
+            (void)hipEventDestroy(ev.first);
+            return;
+        }
+    }
+    if (hipEventRecord(ev.first, st) != hipSuccess) {
+        g_free_events.push_back(ev);
+        return;
+    }
+    g_launches.push_back({width, ev.first, ev.second});
+    g_open_stop = ev.second;
+}
+
+void timing_end(hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    if (g_open_stop) (void)hipEventRecord(g_open_stop, st);
+    g_open_stop = nullptr;
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+// ------------------------------------------------------------------------------------------- objects
+struct gcn_graph {
+    int64_t n = 0, nnz_in = 0, E = 0, E_p = 0, n_train = 0;
+    int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
+    int store_dtype = GCN_F32;
+    PrepBuffers pb{};
+    float *x = nullptr;          // (n + 1) x ldf, zero padded, last row zero
+    int32_t *labels = nullptr;
+    uint8_t *mask = nullptr;
+};
+
+struct Layer {
+    int d_in, d_out, ld_in, ld_out;
+    float *w;    // ld_in x ld_out
+    float *dw;   // ld_in x ld_out
+    float *t;    // (n + 1) x ld_out : D^-1/2 (H_{l-1} W_l), row n zero
+    float *h;    // n x ld_out : H_l (l < L) or the logits (l = L)
+    float *dzs;  // (n + 1) x ld_out : D^-1/2 dLoss/dZ_l, row n zero
+    float *g;    // n x ld_out : A_hat dLoss/dZ_l
+};
+
+struct gcn_model {
+    const gcn_graph *g = nullptr;
+    int L = 0;
+    int dtype = GCN_F32;
+    std::vector<Layer> layers;
+    float p = 0.f;
+    uint64_t seed = 0, epoch = 0;
+    float *partials = nullptr;
+    size_t partial_floats = 0;
+    double *loss_part = nullptr;
+    long long *corr_part = nullptr;
+    float *result = nullptr;        // [0] loss [1] accuracy
+    long long *result_correct = nullptr;
+    bool have_forward = false, have_loss = false, have_backward = false, trained_forward = false;
+};
+
+namespace {
+
+uint64_t host_mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
+
+void carve_graph(Carver &c, gcn_graph &g) {
+    const int64_t n = g.n, cap = g.nnz_in + n;
+    g.pb.rowptr = c.take<int64_t>(n + 1);
+    g.pb.col = c.take<int32_t>(cap);
+    g.pb.deg = c.take<int32_t>(n);
+    g.pb.dinv = c.take<float>(n);
+    g.pb.rowptr_p = c.take<int64_t>(n + 1);
+    g.pb.col_p = c.take<int32_t>(cap + n * (kRowPad - 1));
+    g.pb.perm = c.take<int32_t>(n);
+    g.pb.scratch = c.take<int32_t>(cap);
+    g.pb.plen = c.take<int32_t>(n);
+    g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
+    g.pb.flags = c.take<int32_t>(16);
+    g.x = c.take<float>((size_t)(n + 1) * g.ldf);
+    g.labels = c.take<int32_t>(n);
+    g.mask = c.take<uint8_t>(n);
+}
+
+void carve_model(Carver &c, gcn_model &m) {
+    const int64_t n = m.g->n;
+    size_t pf = 0;
+    for (auto &ly : m.layers) {
+        ly.w = c.take<float>((size_t)ly.ld_in * ly.ld_out);
+        ly.dw = c.take<float>((size_t)ly.ld_in * ly.ld_out);
+        ly.t = c.take<float>((size_t)(n + 1) * ly.ld_out);
+        ly.h = c.take<float>((size_t)(n + 1) * ly.ld_out);
+        ly.dzs = c.take<float>((size_t)(n + 1) * ly.ld_out);
+        ly.g = c.take<float>((size_t)(n + 1) * ly.ld_out);
+        size_t need = gemm_tn_partial_floats(n, ly.ld_in, ly.ld_out);
+        if (need > pf) pf = need;
+    }
+    m.partial_floats = pf;
+    m.partials = c.take<float>(pf);
+    m.loss_part = c.take<double>(kLossBlocks);
+    m.corr_part = c.take<long long>(kLossBlocks);
+    m.result = c.take<float>(4);
+    m.result_correct = c.take<long long>(2);
+}
+
+int check_dims(int32_t n_layers, const int32_t *dims) {
+    if (n_layers < 1 || n_layers > 16 || !dims) return GCN_EINVAL;
+    for (int l = 0; l <= n_layers; ++l)
+        if (dims[l] < 1 || dims[l] > 256 * 4) return GCN_EINVAL;
+    return GCN_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------- C ABI
+extern "C" {
+
+const char *gcn_last_error(void) { return g_err; }
+
+int gcn_graph_workspace_bytes(int64_t n, int64_t nnz_in, int32_t f, int store_dtype, size_t *bytes) {
+    if (!bytes || n <= 0 || n >= 0x7ffffff0 || nnz_in < 0 || f < 1 || store_dtype != GCN_F32) {
+        set_error("gcn_graph_workspace_bytes: bad argument");
+        return GCN_EINVAL;
+    }
+    gcn_graph g;
+    g.n = n;
+    g.nnz_in = nnz_in;
+    g.f = f;
+    g.ldf = padded_width(f);
+    Carver c(nullptr);
+    carve_graph(c, g);
+    *bytes = c.bytes();
+    return GCN_OK;
+}
+
+int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col,
+                     const float *feat, int32_t f, int store_dtype, const int32_t *labels,
+                     const uint8_t *train_mask, int32_t n_classes, void *workspace, size_t workspace_bytes,
+                     void *stream) {
+    if (out) *out = nullptr;
+    if (!out || !rowptr || (!col && nnz_in > 0) || !feat || !labels || !train_mask || n <= 0 || n >= 0x7ffffff0 ||
+        nnz_in < 0 || f < 1 || n_classes < 1) {
+        set_error("gcn_graph_create: null pointer or bad size");
+        return GCN_EINVAL;
+    }
+    if (store_dtype != GCN_F32) {
+        set_error("gcn_graph_create: only float32 storage is implemented");
+        return GCN_EINVAL;
+    }
+    size_t need = 0;
+    int rc = gcn_graph_workspace_bytes(n, nnz_in, f, store_dtype, &need);
+    if (rc) return rc;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < need) {
+        set_error("gcn_graph_create: workspace missing, misaligned or smaller than %zu bytes", need);
+        return GCN_EWORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    gcn_graph *g = new (std::nothrow) gcn_graph;
+    if (!g) {
+        set_error("out of host memory");
+        return GCN_EINVAL;
+    }
+    g->n = n;
+    g->nnz_in = nnz_in;
+    g->f = f;
+    g->ldf = padded_width(f);
+    g->n_classes = n_classes;
+    g->store_dtype = store_dtype;
+    Carver c(workspace);
+    carve_graph(c, *g);
+    int32_t flags[16];
+
+#define FAIL_IF(expr)            \
+    do {                         \
+        int rc_ = (expr);        \
+        if (rc_) {               \
+            delete g;            \
+            return rc_;          \
+        }                        \
+    } while (0)
+#define HIP_OR_FAIL(call)                                                                       \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess) {                                                                 \
+            set_error("%s failed: %s", #call, hipGetErrorString(e_));                           \
+            delete g;                                                                           \
+            return GCN_EHIP;                                                                    \
+        }                                                                                       \
+    } while (0)
+
+    FAIL_IF(fill_zero(g->pb.flags, 16 * sizeof(int32_t), st));
+    FAIL_IF(prep_validate(n, nnz_in, rowptr, col, g->pb.flags, st));
+    FAIL_IF(prep_labels_mask(n, labels, train_mask, n_classes, g->labels, g->mask, g->pb.flags, st));
+    HIP_OR_FAIL(hipMemcpyAsync(flags, g->pb.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+    HIP_OR_FAIL(hipStreamSynchronize(st));
+    if (flags[0]) {
+        set_error("gcn_graph_create: invalid CSR (%s)", (flags[0] & 1) ? "rowptr" : "column index out of range");
+        delete g;
+        return GCN_EGRAPH;
+    }
+    if (flags[1]) {
+        set_error("gcn_graph_create: a label is outside [0, %d)", n_classes);
+        delete g;
+        return GCN_ELABEL;
+    }
+    if (flags[2] <= 0) {
+        set_error("gcn_graph_create: the train mask is empty");
+        delete g;
+        return GCN_EINVAL;
+    }
+    g->n_train = flags[2];
+
+    FAIL_IF(prep_canonical(n, nnz_in, rowptr, col, g->pb, st));
+    FAIL_IF(prep_schedule(n, g->pb, st));
+    FAIL_IF(pad_rows_f32(feat, n, f, g->x, g->ldf, nullptr, st));
+    FAIL_IF(fill_zero(g->x + (size_t)n * g->ldf, (size_t)g->ldf * sizeof(float), st));
+    int64_t ends[2];
+    HIP_OR_FAIL(hipMemcpyAsync(flags, g->pb.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+    HIP_OR_FAIL(hipMemcpyAsync(&ends[0], g->pb.rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HIP_OR_FAIL(hipMemcpyAsync(&ends[1], g->pb.rowptr_p + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HIP_OR_FAIL(hipStreamSynchronize(st));
+    if (flags[0] & 4) {
+        set_error("gcn_graph_create: the adjacency pattern is not symmetric");
+        delete g;
+        return GCN_EGRAPH;
+    }
+    g->E = ends[0];
+    g->E_p = ends[1];
+    g->max_deg = flags[3];
+#undef FAIL_IF
+#undef HIP_OR_FAIL
+    *out = g;
+    return GCN_OK;
+}
+
+int gcn_graph_destroy(gcn_graph *g) {
+    delete g;
+    return GCN_OK;
+}
+
+int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_train, int32_t *max_degree) {
+    if (!g) {
+        set_error("gcn_graph_info: null graph");
+        return GCN_EINVAL;
+    }
+    if (n) *n = g->n;
+    if (nnz) *nnz = g->E;
+    if (n_train) *n_train = g->n_train;
+    if (max_degree) *max_degree = g->max_deg;
+    return GCN_OK;
+}
+
+int gcn_graph_get_csr(const gcn_graph *g, int64_t *rowptr, int32_t *col, int32_t *deg, float *dinv, void *stream) {
+    if (!g) {
+        set_error("gcn_graph_get_csr: null graph");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (rowptr) GCN_HIP(hipMemcpyAsync(rowptr, g->pb.rowptr, (g->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+    if (col) GCN_HIP(hipMemcpyAsync(col, g->pb.col, g->E * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    if (deg) GCN_HIP(hipMemcpyAsync(deg, g->pb.deg, g->n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    if (dinv) GCN_HIP(hipMemcpyAsync(dinv, g->pb.dinv, g->n * sizeof(float), hipMemcpyDeviceToDevice, st));
+    return GCN_OK;
+}
+
+int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, size_t *bytes) {
+    if (!g || !bytes || width < 1 || width > 1024 || dtype != GCN_F32) {
+        set_error("gcn_aggregate_workspace_bytes: bad argument");
+        return GCN_EINVAL;
+    }
+    Carver c(nullptr);
+    const int ld = padded_width(width);
+    c.take<float>((size_t)(g->n + 1) * ld);
+    c.take<float>((size_t)(g->n + 1) * ld);
+    *bytes = c.bytes();
+    return GCN_OK;
+}
+
+int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *workspace,
+                  size_t workspace_bytes, void *stream) {
+    size_t need = 0;
+    int rc = gcn_aggregate_workspace_bytes(g, width, dtype, &need);
+    if (rc) return rc;
+    if (!in || !out) {
+        set_error("gcn_aggregate: null pointer");
+        return GCN_EINVAL;
+    }
+    if (!workspace || !aligned256(workspace) || workspace_bytes < need) {
+        set_error("gcn_aggregate: workspace missing, misaligned or smaller than %zu bytes", need);
+        return GCN_EWORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    const int ld = padded_width(width);
+    float *t = c.take<float>((size_t)(g->n + 1) * ld);
+    float *z = c.take<float>((size_t)(g->n + 1) * ld);
+    rc = pad_rows_f32(in, g->n, width, t, ld, g->pb.dinv, st);
+    if (rc) return rc;
+    rc = fill_zero(t + (size_t)g->n * ld, (size_t)ld * sizeof(float), st);
+    if (rc) return rc;
+    SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, t, ld, z, ld, width, kEpiNone, 0u, 1.0f, 0ull};
+    rc = spmm_launch(a, st);
+    if (rc) return rc;
+    return unpad_rows_f32(z, ld, g->n, width, out, nullptr, st);
+}
+
+// ------------------------------------------------------------------------------------------- model
+int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes) {
+    if (!g || !bytes || check_dims(n_layers, dims) || dtype != GCN_F32) {
+        set_error("gcn_model_workspace_bytes: bad argument");
+        return GCN_EINVAL;
+    }
+    gcn_model m;
+    m.g = g;
+    m.L = n_layers;
+    for (int l = 0; l < n_layers; ++l)
+        m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
+                                 nullptr, nullptr, nullptr, nullptr, nullptr});
+    Carver c(nullptr);
+    carve_model(c, m);
+    *bytes = c.bytes();
+    return GCN_OK;
+}
+
+int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype,
+                     float dropout_p, uint64_t seed, void *workspace, size_t workspace_bytes, void *stream) {
+    if (out) *out = nullptr;
+    if (!out || !g || check_dims(n_layers, dims)) {
+        set_error("gcn_model_create: null pointer or bad layer widths");
+        return GCN_EINVAL;
+    }
+    if (dtype != GCN_F32) {
+        set_error("gcn_model_create: only float32 is implemented");
+        return GCN_EINVAL;
+    }
+    if (dims[0] != g->f || dims[n_layers] != g->n_classes) {
+        set_error("gcn_model_create: dims[0] must be %d and dims[L] must be %d", g->f, g->n_classes);
+        return GCN_EINVAL;
+    }
+    if (!(dropout_p >= 0.0f && dropout_p < 1.0f)) {
+        set_error("gcn_model_create: dropout_p must be in [0, 1)");
+        return GCN_EINVAL;
+    }
+    size_t need = 0;
+    int rc = gcn_model_workspace_bytes(g, n_layers, dims, dtype, &need);
+    if (rc) return rc;
+    if (!workspace || !aligned256(workspace) || workspace_bytes < need) {
+        set_error("gcn_model_create: workspace missing, misaligned or smaller than %zu bytes", need);
+        return GCN_EWORKSPACE;
+    }
+    gcn_model *m = new (std::nothrow) gcn_model;
+    if (!m) {
+        set_error("out of host memory");
+        return GCN_EINVAL;
+    }
+    m->g = g;
+    m->L = n_layers;
+    m->dtype = dtype;
+    m->p = dropout_p;
+    m->seed = seed;
+    for (int l = 0; l < n_layers; ++l)
+        m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
+                                  nullptr, nullptr, nullptr, nullptr, nullptr});
+    Carver c(workspace);
+    carve_model(c, *m);
+    // zero everything once: padding columns, the extra zero rows and the weights start at zero
+    rc = fill_zero(workspace, need, (hipStream_t)stream);
+    if (rc) {
+        delete m;
+        return rc;
+    }
+    *out = m;
+    return GCN_OK;
+}
+
+int gcn_model_destroy(gcn_model *m) {
+    delete m;
+    return GCN_OK;
+}
+
+int gcn_set_weights(gcn_model *m, const float *flat, int on_host, void *stream) {
+    if (!m || !flat) {
+        set_error("gcn_set_weights: null pointer");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    size_t off = 0;
+    for (auto &ly : m->layers) {
+        const size_t cnt = (size_t)ly.d_in * ly.d_out;
+        if (on_host) {
+            // stage through the (currently idle) gradient buffer, then spread into the padded layout
+            GCN_HIP(hipMemcpyAsync(ly.dw, flat + off, cnt * sizeof(float), hipMemcpyHostToDevice, st));
+            GCN_HIP(hipStreamSynchronize(st));
+            int rc = pad_rows_f32(ly.dw, ly.d_in, ly.d_out, ly.w, ly.ld_out, nullptr, st);
+            if (rc) return rc;
+            GCN_HIP(hipStreamSynchronize(st));
+            rc = fill_zero(ly.dw, (size_t)ly.ld_in * ly.ld_out * sizeof(float), st);
+            if (rc) return rc;
+        } else {
+            int rc = pad_rows_f32(flat + off, ly.d_in, ly.d_out, ly.w, ly.ld_out, nullptr, st);
+            if (rc) return rc;
+        }
+        off += cnt;
+    }
+    m->have_forward = m->have_loss = m->have_backward = false;
+    return GCN_OK;
+}
+
+int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_floats, void *stream) {
+    if (!m || !dst) {
+        set_error("gcn_get_tensor: null pointer");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (which == GCN_T_LOGITS) layer = m->L;
+    if (layer < 1 || layer > m->L) {
+        set_error("gcn_get_tensor: layer %d out of range", layer);
+        return GCN_EINVAL;
+    }
+    const Layer &ly = m->layers[layer - 1];
+    const int64_t n = m->g->n;
+    const float *src = nullptr;
+    int ld = ly.ld_out, cols = ly.d_out;
+    int64_t rows = n;
+    const float *rowdiv = nullptr;
+    bool ok = true;
+    switch (which) {
+        case GCN_T_W: src = ly.w; rows = ly.d_in; break;
+        case GCN_T_DW: src = ly.dw; rows = ly.d_in; ok = m->have_backward; break;
+        case GCN_T_H: src = ly.h; ok = m->have_forward && layer < m->L; break;
+        case GCN_T_LOGITS: src = ly.h; ok = m->have_forward; break;
+        case GCN_T_G: src = ly.g; ok = m->have_backward; break;
+        case GCN_T_DZ: src = ly.dzs; rowdiv = m->g->pb.dinv; ok = m->have_backward; break;
+        default: ok = false;
+    }
+    if (!ok || !src) {
+        set_error("gcn_get_tensor: tensor %d of layer %d is not available now", which, layer);
+        return GCN_EINVAL;
+    }
+    if (dst_floats < (size_t)rows * cols) {
+        set_error("gcn_get_tensor: destination holds %zu floats, %zu needed", dst_floats, (size_t)rows * cols);
+        return GCN_EINVAL;
+    }
+    return unpad_rows_f32(src, ld, rows, cols, dst, rowdiv, st);
+}
+
+int gcn_forward(gcn_model *m, int training, void *stream) {
+    if (!m) {
+        set_error("gcn_forward: null model");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const gcn_graph *g = m->g;
+    const float *h_prev = g->x;
+    int ld_prev = g->ldf;
+    for (int l = 1; l <= m->L; ++l) {
+        Layer &ly = m->layers[l - 1];
+        // T = D^-1/2 (H_{l-1} W_l)
+        int rc = gemm_nn(h_prev, ld_prev, ly.w, ly.ld_out, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out, g->pb.dinv, st);
+        if (rc) return rc;
+        // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]
+        SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, ly.t, ly.ld_out, ly.h, ly.ld_out,
+                   ly.d_out, l < m->L ? kEpiRelu : kEpiNone, 0u, 1.0f, 0ull};
+        if (l < m->L && training && m->p > 0.0f) {
+            a.drop_threshold = (uint32_t)std::floor((double)m->p * 4294967296.0);
+            a.keep_scale = (float)(1.0 / (1.0 - (double)m->p));
+            a.drop_key = host_mix64(host_mix64(m->seed) ^ (m->epoch * 0xD1B54A32D192ED03ull) ^
+                                    ((uint64_t)l * 0x8CB92BA72F3D8DD7ull));
+        }
+        rc = spmm_launch(a, st);
+        if (rc) return rc;
+        h_prev = ly.h;
+        ld_prev = ly.ld_out;
+    }
+    m->have_forward = true;
+    m->trained_forward = training && m->p > 0.0f;
+    m->have_loss = m->have_backward = false;
+    return GCN_OK;
+}
+
+int gcn_loss_acc(gcn_model *m, float *loss, float *acc, void *stream) {
+    if (!m || !m->have_forward) {
+        set_error("gcn_loss_acc: call gcn_forward first");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const gcn_graph *g = m->g;
+    Layer &ly = m->layers[m->L - 1];
+    int rc = loss_forward(g->n, ly.d_out, ly.h, ly.ld_out, g->labels, g->mask, g->pb.dinv, g->n_train, ly.dzs,
+                          ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st);
+    if (rc) return rc;
+    m->have_loss = true;
+    if (loss || acc) {
+        float host[2];
+        GCN_HIP(hipMemcpyAsync(host, m->result, sizeof(host), hipMemcpyDeviceToHost, st));
+        GCN_HIP(hipStreamSynchronize(st));
+        if (loss) *loss = host[0];
+        if (acc) *acc = host[1];
+    }
+    return GCN_OK;
+}
+
+int gcn_loss_acc_counts(gcn_model *m, int64_t *correct, int64_t *n_train, void *stream) {
+    if (!m || !m->have_loss) {
+        set_error("gcn_loss_acc_counts: call gcn_loss_acc first");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    long long host = 0;
+    GCN_HIP(hipMemcpyAsync(&host, m->result_correct, sizeof(host), hipMemcpyDeviceToHost, st));
+    GCN_HIP(hipStreamSynchronize(st));
+    if (correct) *correct = (int64_t)host;
+    if (n_train) *n_train = m->g->n_train;
+    return GCN_OK;
+}
+
+int gcn_backward(gcn_model *m, void *stream) {
+    if (!m || !m->have_forward || !m->have_loss) {
+        set_error("gcn_backward: call gcn_forward and gcn_loss_acc first");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const gcn_graph *g = m->g;
+    const float keep_scale = m->trained_forward ? (float)(1.0 / (1.0 - (double)m->p)) : 1.0f;
+    for (int l = m->L; l >= 1; --l) {
+        Layer &ly = m->layers[l - 1];
+        // G = A_hat dZ_l  (dzs already carries D^-1/2)
+        SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, ly.dzs, ly.ld_out, ly.g, ly.ld_out,
+                   ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
+        int rc = spmm_launch(a, st);
+        if (rc) return rc;
+        // dW_l = H_{l-1}^T G
+        const float *h_prev = l > 1 ? m->layers[l - 2].h : g->x;
+        rc = gemm_tn(h_prev, ly.ld_in, ly.g, ly.ld_out, ly.dw, ly.ld_out, g->n, ly.ld_in, ly.ld_out, m->partials,
+                     m->partial_floats, st);
+        if (rc) return rc;
+        if (l > 1) {
+            // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
+            Layer &lp = m->layers[l - 2];
+            rc = gemm_nt(ly.g, ly.ld_out, ly.w, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out, g->pb.dinv,
+                         lp.h, lp.ld_out, keep_scale, st);
+            if (rc) return rc;
+        }
+    }
+    m->have_backward = true;
+    return GCN_OK;
+}
+
+int gcn_sgd_step(gcn_model *m, float lr, void *stream) {
+    if (!m || !m->have_backward) {
+        set_error("gcn_sgd_step: call gcn_backward first");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (auto &ly : m->layers) {
+        int rc = sgd_update(ly.w, ly.dw, (size_t)ly.ld_in * ly.ld_out, lr, st);
+        if (rc) return rc;
+    }
+    m->epoch += 1;
+    m->have_forward = m->have_loss = m->have_backward = false;
+    return GCN_OK;
+}
+
+// ------------------------------------------------------------------------------------------- timing
+int gcn_timing_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    g_timing = on != 0;
+    return GCN_OK;
+}
+
+int gcn_timing_reset(void) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    for (auto &t : g_launches) g_free_events.push_back({t.start, t.stop});
+    g_launches.clear();
+    return GCN_OK;
+}
+
+int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    int64_t cnt = 0;
+    double ms = 0.0;
+    for (auto &t : g_launches) {
+        if (t.width != width) continue;
+        GCN_HIP(hipEventSynchronize(t.stop));
+        float one = 0.f;
+        GCN_HIP(hipEventElapsedTime(&one, t.start, t.stop));
+        ms += one;
+        ++cnt;
+    }
+    if (launches) *launches = cnt;
+    if (total_ms) *total_ms = ms;
+    return GCN_OK;
+}
+
+}  // extern "C"

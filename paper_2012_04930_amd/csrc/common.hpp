@@ -1,0 +1,141 @@
+// Internal declarations shared by the translation units of libgcn355.so (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "../../include/gcn355.h"
+
+namespace gcn {
+
+void set_error(const char *fmt, ...);
+
+#define GCN_HIP(call)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            gcn::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return GCN_EHIP;                                                                   \
+        }                                                                                      \
+    } while (0)
+
+#define GCN_LAUNCH_CHECK()                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = hipGetLastError();                                                     \
+        if (e_ != hipSuccess) {                                                                \
+            gcn::set_error("kernel launch failed: %s (%s:%d)", hipGetErrorString(e_), __FILE__, __LINE__); \
+            return GCN_EHIP;                                                                   \
+        }                                                                                      \
+    } while (0)
+
+constexpr int kWave = 64;
+constexpr int kLdAlign = 16;   // leading dimensions are multiples of 16 elements (64 B in fp32)
+constexpr int kRowPad = 8;     // scheduled rows are padded to a multiple of 8 entries
+constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int padded_width(int w) { return (int)round_up(w, kLdAlign); }
+
+// Bump allocator over a caller workspace; with base == nullptr it only measures.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *b) : base((char *)b) {}
+    template <typename T>
+    T *take(size_t count) {
+        off = (off + 255) & ~(size_t)255;
+        T *p = base ? (T *)(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+    size_t bytes() const { return (off + 255) & ~(size_t)255; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Graph preparation (prep.hip)
+struct PrepBuffers {
+    // canonical pattern of A + I
+    int64_t *rowptr;   // n + 1
+    int32_t *col;      // <= nnz_in + n
+    int32_t *deg;      // n
+    float *dinv;       // n
+    // schedule: rows in processing order, each padded to a multiple of kRowPad with column n
+    int64_t *rowptr_p; // n + 1
+    int32_t *col_p;    // <= nnz_in + n + n * (kRowPad - 1)
+    int32_t *perm;     // n   slot -> row
+    // scratch
+    int32_t *scratch;  // nnz_in + n
+    int32_t *plen;     // n
+    int64_t *blocksum; // scan partials
+    int32_t *flags;    // 16 ints: [0] graph error, [1] label error, [2] n_train, [3] max degree
+};
+
+int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, int32_t *flags,
+                  hipStream_t st);
+int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, PrepBuffers &pb,
+                   hipStream_t st);
+int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
+int prep_labels_mask(int64_t n, const int32_t *labels, const uint8_t *mask, int32_t n_classes, int32_t *labels_out,
+                     uint8_t *mask_out, int32_t *flags, hipStream_t st);
+size_t scan_blocks(int64_t n);
+
+// ---------------------------------------------------------------------------------------------
+// Layout helpers (elementwise.hip).  "padded" = row-major with leading dimension ld >= width, pad zero.
+int pad_rows_f32(const float *src, int64_t rows, int width, float *dst, int ld, const float *rowscale, hipStream_t st);
+int unpad_rows_f32(const float *src, int ld, int64_t rows, int width, float *dst, const float *rowdiv, hipStream_t st);
+int fill_zero(void *p, size_t bytes, hipStream_t st);
+
+// Loss / accuracy / dLoss/dlogits (scaled by dinv for the aggregation that follows).
+constexpr int kLossBlocks = 512;
+int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
+                 const float *dinv, int64_t n_train, float *dzs, int ld_dz, double *loss_part, long long *corr_part,
+                 float *result /* [0] loss, [1] accuracy, as float */, long long *result_correct, hipStream_t st);
+int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Aggregation (spmm.hip):  out[r, :] = dinv[r] * sum over the scheduled row of r of  t[col, :],
+// where t already carries the factor dinv[col] and has an all-zero row n for the padding entries.
+enum SpmmEpilogue { kEpiNone = 0, kEpiRelu = 1 };
+struct SpmmArgs {
+    const int64_t *rowptr_p;
+    const int32_t *col_p;
+    const int32_t *perm;
+    const float *dinv;
+    int64_t n;
+    const float *t;
+    int ld_t;
+    float *out;
+    int ld_out;
+    int width;          // true width (<= ld)
+    int epilogue;
+    // dropout (epilogue kEpiRelu, training): threshold 0 = keep everything
+    uint32_t drop_threshold;
+    float keep_scale;
+    uint64_t drop_key;
+};
+int spmm_launch(const SpmmArgs &a, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Dense products on the matrix cores (gemm.hip).  All leading dimensions are multiples of 16 and the
+// padding columns/rows of the operands are zero.
+//   nn:  c[m, :] = rowscale[m] * (a[m, :] b)                a: M x K,  b: K x N,  c: M x N
+//   nt:  c[m, :] = rowscale[m] * scale * [gate[m, :] > 0] * (a[m, :] b^T)      b: N x K
+//   tn:  c = a^T b  reduced over the M rows of a and b in fixed order (split over row ranges)
+int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
+            const float *rowscale, hipStream_t st);
+int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
+            const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st);
+size_t gemm_tn_partial_floats(int64_t rows, int M, int N);
+int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t rows, int M, int N,
+            float *partials, size_t partial_floats, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Event timing of aggregation launches (api.hip)
+void timing_begin(int width, hipStream_t st);
+void timing_end(hipStream_t st);
+
+}  // namespace gcn

@@ -1,0 +1,208 @@
+// Layout copies, the masked softmax cross-entropy with accuracy, and the SGD update.
+//
+// Task and metric: vertex classification scored by micro-F1, i.e. accuracy for one label per
+// vertex (Section 2.2).  The paper does not print its loss; this is the softmax cross-entropy of
+// the cited Kipf-Welling model, averaged over the train mask.  Update: plain SGD.
+#include "common.hpp"
+
+namespace gcn {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ void k_pad_rows(const float *__restrict__ src, int64_t rows, int width, float *__restrict__ dst, int ld,
+                           const float *__restrict__ rowscale) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = rows * ld;
+    if (t >= total) return;
+    int64_t r = t / ld;
+    int c = (int)(t - r * ld);
+    float v = c < width ? src[r * width + c] : 0.0f;
+    if (rowscale) v *= rowscale[r];
+    dst[t] = v;
+}
+
+__global__ void k_unpad_rows(const float *__restrict__ src, int ld, int64_t rows, int width, float *__restrict__ dst,
+                             const float *__restrict__ rowdiv) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = rows * width;
+    if (t >= total) return;
+    int64_t r = t / width;
+    int c = (int)(t - r * width);
+    float v = src[r * ld + c];
+    if (rowdiv) v /= rowdiv[r];
+    dst[t] = v;
+}
+
+__global__ void k_fill_zero(uint32_t *__restrict__ p, size_t words) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; t < words; t += stride) p[t] = 0u;
+}
+
+// One wave per vertex, waves stride over the vertices in a fixed pattern, so every partial sum
+// is made of the same terms in the same order on every run.
+__global__ __launch_bounds__(kThreads) void k_loss(int64_t n, int classes, const float *__restrict__ logits, int ld,
+                                                   const int32_t *__restrict__ labels,
+                                                   const uint8_t *__restrict__ mask, const float *__restrict__ dinv,
+                                                   float inv_ntrain, float *__restrict__ dzs, int ld_dz,
+                                                   double *__restrict__ loss_part,
+                                                   long long *__restrict__ corr_part) {
+    __shared__ double s_loss[kThreads / 64];
+    __shared__ long long s_corr[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t waves_total = (int64_t)gridDim.x * (kThreads / 64);
+    double my_loss = 0.0;
+    long long my_corr = 0;
+    for (int64_t v = (int64_t)blockIdx.x * (kThreads / 64) + wave; v < n; v += waves_total) {
+        const float *z = logits + v * ld;
+        float *g = dzs + v * ld_dz;
+        if (!mask[v]) {
+            for (int c = lane; c < classes; c += 64) g[c] = 0.0f;
+            continue;
+        }
+        // maximum and its lowest index
+        float m = -INFINITY;
+        int arg = 0x7fffffff;
+        for (int c = lane; c < classes; c += 64) {
+            float x = z[c];
+            if (x > m) {
+                m = x;
+                arg = c;
+            }
+        }
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            float om = __shfl_xor(m, d, 64);
+            int oa = __shfl_xor(arg, d, 64);
+            if (om > m || (om == m && oa < arg)) {
+                m = om;
+                arg = oa;
+            }
+        }
+        float s = 0.0f;
+        for (int c = lane; c < classes; c += 64) s += expf(z[c] - m);
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, 64);
+        const float lse = m + logf(s);
+        const int y = labels[v];
+        const float scale = dinv[v] * inv_ntrain;
+        for (int c = lane; c < classes; c += 64) {
+            float p = expf(z[c] - lse);
+            g[c] = (p - (c == y ? 1.0f : 0.0f)) * scale;
+        }
+        if (lane == 0) {
+            my_loss += (double)(lse - z[y]);
+            my_corr += (arg == y) ? 1 : 0;
+        }
+    }
+    if (lane == 0) {
+        s_loss[wave] = my_loss;
+        s_corr[wave] = my_corr;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0;
+        long long c = 0;
+        for (int w = 0; w < kThreads / 64; ++w) {
+            a += s_loss[w];
+            c += s_corr[w];
+        }
+        loss_part[blockIdx.x] = a;
+        corr_part[blockIdx.x] = c;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_loss_final(int parts, const double *__restrict__ loss_part,
+                                                         const long long *__restrict__ corr_part, double inv_ntrain,
+                                                         float *__restrict__ result,
+                                                         long long *__restrict__ result_correct) {
+    __shared__ double s_loss[kThreads];
+    __shared__ long long s_corr[kThreads];
+    double a = 0.0;
+    long long c = 0;
+    for (int p = threadIdx.x; p < parts; p += kThreads) {
+        a += loss_part[p];
+        c += corr_part[p];
+    }
+    s_loss[threadIdx.x] = a;
+    s_corr[threadIdx.x] = c;
+    __syncthreads();
+    for (int d = kThreads / 2; d > 0; d >>= 1) {
+        if (threadIdx.x < d) {
+            s_loss[threadIdx.x] += s_loss[threadIdx.x + d];
+            s_corr[threadIdx.x] += s_corr[threadIdx.x + d];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        result[0] = (float)(s_loss[0] * inv_ntrain);
+        result[1] = (float)((double)s_corr[0] * inv_ntrain);
+        *result_correct = s_corr[0];
+    }
+}
+
+__global__ void k_sgd(float *__restrict__ w, const float *__restrict__ dw, size_t count, float lr) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < count) w[t] = w[t] - lr * dw[t];
+}
+
+inline unsigned blocks_for(int64_t items, int per_block) { return (unsigned)((items + per_block - 1) / per_block); }
+
+}  // namespace
+
+int pad_rows_f32(const float *src, int64_t rows, int width, float *dst, int ld, const float *rowscale,
+                 hipStream_t st) {
+    if (rows <= 0) return GCN_OK;
+    k_pad_rows<<<dim3(blocks_for(rows * ld, kThreads)), dim3(kThreads), 0, st>>>(src, rows, width, dst, ld, rowscale);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int unpad_rows_f32(const float *src, int ld, int64_t rows, int width, float *dst, const float *rowdiv,
+                   hipStream_t st) {
+    if (rows <= 0) return GCN_OK;
+    k_unpad_rows<<<dim3(blocks_for(rows * width, kThreads)), dim3(kThreads), 0, st>>>(src, ld, rows, width, dst,
+                                                                                      rowdiv);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int fill_zero(void *p, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return GCN_OK;
+    if (bytes % 4 != 0) {
+        set_error("fill_zero: size not a multiple of 4");
+        return GCN_EINVAL;
+    }
+    size_t words = bytes / 4;
+    unsigned blocks = (unsigned)((words + kThreads - 1) / kThreads);
+    if (blocks > 65536u) blocks = 65536u;
+    k_fill_zero<<<dim3(blocks), dim3(kThreads), 0, st>>>((uint32_t *)p, words);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
+                 const float *dinv, int64_t n_train, float *dzs, int ld_dz, double *loss_part, long long *corr_part,
+                 float *result, long long *result_correct, hipStream_t st) {
+    int blocks = (int)((n + 3) / 4);
+    if (blocks > kLossBlocks) blocks = kLossBlocks;
+    if (blocks < 1) blocks = 1;
+    k_loss<<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv,
+                                                    (float)(1.0 / (double)n_train), dzs, ld_dz, loss_part, corr_part);
+    GCN_LAUNCH_CHECK();
+    k_loss_final<<<dim3(1), dim3(kThreads), 0, st>>>(blocks, loss_part, corr_part, 1.0 / (double)n_train, result,
+                                                     result_correct);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st) {
+    if (count == 0) return GCN_OK;
+    k_sgd<<<dim3(blocks_for((int64_t)count, kThreads)), dim3(kThreads), 0, st>>>(w, dw, count, lr);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+}  // namespace gcn

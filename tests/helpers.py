@@ -1,0 +1,89 @@
+"""Shared pieces of the GPU-vs-oracle parity tests."""
+import numpy as np
+import torch
+
+RTOL_F32 = 1e-4     # relative tolerance on logits, loss and gradients in fp32 (the stated bar)
+
+
+def assert_close(gpu, ref, rtol=RTOL_F32, what=""):
+    """max_i |gpu_i - ref_i| <= rtol * max(|ref_i|, rms(ref)), element by element."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    assert np.all(np.isfinite(gpu)), what + ": non-finite values"
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    bound = rtol * np.maximum(np.abs(ref), rms)
+    err = np.abs(gpu - ref)
+    worst = int(np.argmax(err - bound)) if err.size else 0
+    assert np.all(err <= bound), "%s: |diff| %.3e > bound %.3e at flat index %d (ref %.6e, rms %.3e)" % (
+        what, err.flat[worst], bound.flat[worst], worst, ref.flat[worst], rms)
+
+
+def to_dev(wl):
+    """Workload arrays as device tensors in the types the C ABI takes."""
+    return dict(
+        rowptr=torch.from_numpy(np.ascontiguousarray(wl.rowptr, dtype=np.int64)).cuda(),
+        col=torch.from_numpy(np.ascontiguousarray(wl.col, dtype=np.int32)).cuda(),
+        x=torch.from_numpy(np.ascontiguousarray(wl.x, dtype=np.float32)).cuda(),
+        labels=torch.from_numpy(np.ascontiguousarray(wl.labels, dtype=np.int32)).cuda(),
+        mask=torch.from_numpy(np.ascontiguousarray(wl.mask, dtype=np.uint8)).cuda(),
+    )
+
+
+def gpu_graph(B, wl):
+    d = to_dev(wl)
+    g = B.gcn_graph_create(d["rowptr"], d["col"], d["x"], d["labels"], d["mask"], wl.dims[-1])
+    return g
+
+
+def gpu_epoch(B, g, wl, lr=None, dropout_p=0.0, seed=0, training=True, epochs_before=0):
+    """One epoch on the GPU; returns the model and a dict of every observable tensor (numpy)."""
+    m = B.gcn_model_create(g, wl.dims, dropout_p=dropout_p, seed=seed)
+    B.gcn_set_weights(m, wl.weights)
+    nl = len(wl.dims) - 1
+    out = {}
+    B.gcn_forward(m, training)
+    out["H"] = [B.gcn_get_tensor(m, B.GCN_T_H, l).cpu().numpy() for l in range(1, nl)]
+    out["logits"] = B.gcn_get_tensor(m, B.GCN_T_LOGITS).cpu().numpy()
+    out["loss"], out["acc"] = B.gcn_loss_acc(m)
+    out["correct"], out["n_train"] = B.gcn_loss_acc_counts(m)
+    B.gcn_backward(m)
+    out["G"] = [B.gcn_get_tensor(m, B.GCN_T_G, l).cpu().numpy() for l in range(1, nl + 1)]
+    out["dZ"] = [B.gcn_get_tensor(m, B.GCN_T_DZ, l).cpu().numpy() for l in range(1, nl + 1)]
+    out["dW"] = [B.gcn_get_tensor(m, B.GCN_T_DW, l).cpu().numpy() for l in range(1, nl + 1)]
+    B.gcn_sgd_step(m, wl.lr if lr is None else lr)
+    out["W"] = [B.gcn_get_tensor(m, B.GCN_T_W, l).cpu().numpy() for l in range(1, nl + 1)]
+    torch.cuda.synchronize()
+    return m, out
+
+
+def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True):
+    og = O.canonicalise(wl.n, wl.rowptr, wl.col)
+    ws = [w.astype(np.float64) for w in wl.weights]
+    tr = O.forward(og, wl.x, ws, p=dropout_p, training=training, seed=seed, epoch=0)
+    O.backward(og, tr, ws, wl.labels, wl.mask, p=dropout_p if training else 0.0)
+    new = O.sgd(ws, tr.dW, wl.lr if lr is None else lr)
+    return og, tr, new
+
+
+def compare_epoch(O, wl, gpu, tr, new_w, rtol=RTOL_F32):
+    nl = len(wl.dims) - 1
+    for l in range(1, nl):
+        assert_close(gpu["H"][l - 1], tr.H[l], rtol, "H%d" % l)
+    assert_close(gpu["logits"], tr.Z[-1], rtol, "logits")
+    assert abs(gpu["loss"] - tr.loss) <= rtol * abs(tr.loss), ("loss", gpu["loss"], tr.loss)
+    # accuracy is an integer decided by floating point: both sides decide on the same fp32 logits
+    _, correct_on_gpu_logits, n_train, _ = O.loss_acc(gpu["logits"].astype(np.float64), wl.labels, wl.mask,
+                                                      want_grad=False)
+    assert gpu["n_train"] == n_train == tr.n_train
+    assert gpu["correct"] == correct_on_gpu_logits, ("correct", gpu["correct"], correct_on_gpu_logits)
+    assert abs(gpu["acc"] - gpu["correct"] / n_train) < 1e-6
+    # and the oracle's own count may differ only on vertices whose two best logits nearly tie
+    z = np.sort(tr.Z[-1][wl.mask.astype(bool)], axis=1)
+    near_ties = int(np.sum((z[:, -1] - z[:, -2]) <= 2 * rtol * np.maximum(np.abs(z[:, -1]), 1e-3)))
+    assert abs(gpu["correct"] - tr.correct) <= near_ties
+    for l in range(1, nl + 1):
+        assert_close(gpu["dZ"][l - 1], tr.dZ[l - 1], rtol, "dZ%d" % l)
+        assert_close(gpu["G"][l - 1], tr.G[l - 1], rtol, "G%d" % l)
+        assert_close(gpu["dW"][l - 1], tr.dW[l - 1], rtol, "dW%d" % l)
+        assert_close(gpu["W"][l - 1], new_w[l - 1], rtol, "W%d after SGD" % l)

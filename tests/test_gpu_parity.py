@@ -1,0 +1,205 @@
+"""GPU library vs CPU oracle, element by element, on the same seeded inputs (run with -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from synth import graphs, rng, workloads
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2012_04930_amd import binding
+    binding.lib()
+    return binding
+
+
+def _heavy_row_workload(n=6000, heavy=(0, 17), seed=3):
+    """Small random graph plus two vertices adjacent to almost everyone: rows longer than the
+    in-LDS sort limit, so the bit-set path of the canonicalisation is exercised."""
+    m = 3 * n
+    rowptr, col = graphs.erdos_renyi_gnm(n, m, seed)
+    deg = np.diff(rowptr)
+    rows = np.repeat(np.arange(n, dtype=np.int64), deg)
+    u = [rows, ]
+    v = [col.astype(np.int64), ]
+    for hv in heavy:
+        others = np.nonzero(rng.uniform(seed, 50 + hv, n) < 0.9)[0]
+        u.append(np.full(others.size, hv, dtype=np.int64))
+        v.append(others)
+    rp, cl = graphs.pairs_to_csr(n, np.concatenate(u), np.concatenate(v))
+    return graphs.messy_copy(n, rp, cl, seed)
+
+
+# ------------------------------------------------------------------ graph preparation: bit-exact
+@pytest.mark.parametrize("case", ["tiny_messy", "heavy_rows", "isolated", "partition"])
+def test_graph_preparation_is_bit_exact(B, oracle, case):
+    if case == "tiny_messy":
+        wl = workloads.tiny(messy=True)
+    elif case == "heavy_rows":
+        wl = workloads.tiny(n=6000)
+        wl.rowptr, wl.col = _heavy_row_workload()
+    elif case == "isolated":
+        wl = workloads.tiny(n=300)
+        wl.rowptr = np.zeros(301, dtype=np.int64)
+        wl.col = np.zeros(0, dtype=np.int32)
+    else:
+        wl = workloads.reddit_partition(scale=0.05)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    g = H.gpu_graph(B, wl)
+    info = B.gcn_graph_info(g)
+    assert info["n"] == wl.n and info["nnz"] == int(og.rowptr[-1])
+    assert info["n_train"] == int(wl.mask.sum()) and info["max_degree"] == int(og.deg.max())
+    rowptr, col, deg, dinv = [t.cpu().numpy() for t in B.gcn_graph_get_csr(g)]
+    np.testing.assert_array_equal(rowptr, og.rowptr)
+    np.testing.assert_array_equal(col, og.col)
+    np.testing.assert_array_equal(deg, og.deg)
+    np.testing.assert_allclose(dinv, og.dinv, rtol=1e-7)
+
+
+def test_graph_errors_are_reported_not_raised_by_the_gpu(B):
+    wl = workloads.tiny(n=256)
+    d = H.to_dev(wl)
+    args = lambda **kw: {**d, **kw}
+
+    def create(a):
+        return B.gcn_graph_create(a["rowptr"], a["col"], a["x"], a["labels"], a["mask"], wl.dims[-1])
+
+    bad_col = d["col"].clone()
+    bad_col[5] = wl.n
+    with pytest.raises(B.GcnError) as e:
+        create(args(col=bad_col))
+    assert e.value.code == -2
+    bad_rp = d["rowptr"].clone()
+    bad_rp[10] = bad_rp[11] + 1
+    with pytest.raises(B.GcnError) as e:
+        create(args(rowptr=bad_rp))
+    assert e.value.code == -2
+    # one direction of an edge removed: no longer symmetric
+    rp, cl = wl.rowptr.copy(), wl.col.copy()
+    first = int(np.nonzero(np.diff(rp))[0][0])
+    cl = np.delete(cl, rp[first])
+    rp[first + 1:] -= 1
+    with pytest.raises(B.GcnError) as e:
+        create(args(rowptr=torch.from_numpy(rp).cuda(), col=torch.from_numpy(cl).cuda()))
+    assert e.value.code == -2
+    bad_lab = d["labels"].clone()
+    bad_lab[3] = wl.dims[-1]
+    with pytest.raises(B.GcnError) as e:
+        create(args(labels=bad_lab))
+    assert e.value.code == -3
+    with pytest.raises(B.GcnError) as e:
+        create(args(mask=torch.zeros_like(d["mask"])))
+    assert e.value.code == -1
+    g = create(d)
+    m = B.gcn_model_create(g, wl.dims)
+    with pytest.raises(B.GcnError) as e:
+        B.gcn_backward(m)                      # before forward
+    assert e.value.code == -1
+    with pytest.raises(B.GcnError):
+        B.gcn_model_create(g, [wl.dims[0] + 1, 4, wl.dims[-1]])
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ aggregation alone
+@pytest.mark.parametrize("width", [1, 7, 16, 41, 100, 128, 200, 256])
+def test_aggregate_matches_oracle(B, oracle, width):
+    wl = workloads.chung_lu_mid(scale=0.03)          # 3,000 vertices, ragged degrees 1..~150
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(width, 1, wl.n * width).reshape(wl.n, width)
+    got = B.gcn_aggregate(g, torch.from_numpy(x).cuda()).cpu().numpy()
+    H.assert_close(got, oracle.aggregate(og, x), what="A_hat x, width %d" % width)
+
+
+def test_aggregate_heavy_rows_and_regular_invariant(B, oracle):
+    wl = workloads.tiny(n=6000)
+    wl.rowptr, wl.col = _heavy_row_workload()
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(9, 1, wl.n * 48).reshape(wl.n, 48)
+    got = B.gcn_aggregate(g, torch.from_numpy(x).cuda()).cpu().numpy()
+    H.assert_close(got, oracle.aggregate(og, x), what="heavy rows")
+    # A_hat sqrt(d) = sqrt(d): holds at any size
+    sq = np.sqrt(og.deg.astype(np.float64)).astype(np.float32)[:, None].repeat(4, 1)
+    got = B.gcn_aggregate(g, torch.from_numpy(np.ascontiguousarray(sq)).cuda()).cpu().numpy()
+    np.testing.assert_allclose(got, sq, rtol=2e-5)
+
+
+# ------------------------------------------------------------------ the whole step
+def test_tiny_config_full_step(B, oracle):
+    wl = workloads.tiny()                              # config 1
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+@pytest.mark.parametrize("make", [lambda: workloads.chung_lu_mid(scale=0.1),
+                                  lambda: workloads.reddit_partition(scale=0.08),
+                                  lambda: workloads.rmat_large(scale=0.004)],
+                         ids=["chung_lu_10k", "partition_3.7k", "rmat_9.6k_3layers"])
+def test_mid_configs_full_step(B, oracle, make):
+    wl = make()
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+def test_zero_last_layer_gives_log_c_and_closed_form_gradient(B):
+    wl = workloads.tiny(n=1000)
+    wl.weights[-1][:] = 0.0
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    assert abs(gpu["loss"] - np.log(7.0)) < 1e-6
+    m = wl.mask.astype(bool)
+    assert gpu["correct"] == int(np.sum(wl.labels[m] == 0))
+    want = m[:, None] * (1.0 / 7 - np.eye(7)[wl.labels]) / m.sum()
+    H.assert_close(gpu["dZ"][-1], want, what="dZ_L at W_L = 0")
+
+
+def test_two_epochs_and_determinism(B, oracle):
+    wl = workloads.chung_lu_mid(scale=0.05)
+    g = H.gpu_graph(B, wl)
+    runs = []
+    for _ in range(2):
+        m = B.gcn_model_create(g, wl.dims)
+        B.gcn_set_weights(m, wl.weights)
+        losses = []
+        for _e in range(3):
+            B.gcn_forward(m, True)
+            losses.append(B.gcn_loss_acc(m)[0])
+            B.gcn_backward(m)
+            B.gcn_sgd_step(m, 0.5)
+        runs.append((losses, [B.gcn_get_tensor(m, B.GCN_T_W, l).cpu().numpy() for l in (1, 2)]))
+    assert runs[0][0] == runs[1][0]
+    for a, b in zip(runs[0][1], runs[1][1]):
+        np.testing.assert_array_equal(a, b)                      # no float atomics anywhere: bit-identical
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    ws = [w.astype(np.float64) for w in wl.weights]
+    ref_losses = []
+    for _e in range(3):
+        ws, tr = oracle.train_epoch(og, wl.x, ws, wl.labels, wl.mask, lr=0.5)
+        ref_losses.append(tr.loss)
+    np.testing.assert_allclose(runs[0][0], ref_losses, rtol=1e-4)
+    for a, b in zip(runs[0][1], ws):
+        H.assert_close(a, b, what="weights after 3 epochs")
+
+
+def test_dropout_mask_and_scaling(B, oracle):
+    wl = workloads.chung_lu_mid(scale=0.02)
+    g = H.gpu_graph(B, wl)
+    p, seed = 0.4, 12345
+    _, gpu = H.gpu_epoch(B, g, wl, dropout_p=p, seed=seed, training=True)
+    _, tr, new = H.oracle_epoch(oracle, wl, dropout_p=p, seed=seed, training=True)
+    keep = oracle.dropout_keep(seed, 0, 1, wl.n, wl.dims[1], p)
+    assert np.all(gpu["H"][0][keep == 0] == 0.0)                  # same mask, bit for bit
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+    # evaluation mode ignores dropout
+    _, gpu_eval = H.gpu_epoch(B, g, wl, dropout_p=p, seed=seed, training=False)
+    _, tr_eval, _ = H.oracle_epoch(oracle, wl, dropout_p=p, seed=seed, training=False)
+    H.assert_close(gpu_eval["logits"], tr_eval.Z[-1], what="eval logits")
