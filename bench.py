@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark: full-batch GCN training epochs per second on one partition, one MI355X.
+
+One step = one epoch = gcn_forward + gcn_loss_acc + gcn_backward + gcn_sgd_step over the whole
+partition (graph creation is outside the timed region; all inputs are resident in HBM).
+Prints ONE JSON line with the epoch rate, the roofline position of the dominant kernel (the
+width-d_1 aggregation) measured with HIP events inside the timed region, and the CPU oracle
+timed on this machine's host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak
+FP32_PEAK_TFLOPS = 157.3
+
+
+def gather_bytes(E: int, n: int, w: int, s: int = 4) -> int:
+    """Algorithmic traffic of one aggregation of width w: every nonzero pulls a 4-byte column index
+    and one feature row, every output row is written once, plus the row pointers and d^-1/2."""
+    return E * (4 + w * s) + n * w * s + 8 * (n + 1) + 4 * n
+
+
+def read_traffic(workload: str, width: int):
+    """HBM bytes per launch of the aggregation kernel measured with rocprofv3 counters, if a
+    summary for this workload has been committed under profiles/ (else None)."""
+    path = os.path.join(ROOT, "profiles", "spmm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 3 and parts[0] == workload and parts[1] == "w%d" % width:
+            try:
+                return float(parts[2])
+            except ValueError:
+                return None
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain copy kernel of this many MiB (scales rocprofv3 byte counters)")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket aggregation launches with events")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (one partition = one worker's share of the "
+              "data-parallel scheme); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2012_04930_amd import binding as B
+    from synth import workloads
+    from tests import helpers as H
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    t0 = time.perf_counter()
+    wl = workloads.BY_NAME[args.workload](seed=args.seed)
+    t_gen = time.perf_counter() - t0
+    if wl.dtype != "f32":
+        print("bench.py: workload %s needs bf16 storage, which this build does not have yet" % args.workload,
+              file=sys.stderr)
+        return 2
+
+    t0 = time.perf_counter()
+    g = H.gpu_graph(B, wl)
+    torch.cuda.synchronize()
+    t_create = time.perf_counter() - t0
+    info = B.gcn_graph_info(g)
+    m = B.gcn_model_create(g, wl.dims)
+    B.gcn_set_weights(m, wl.weights)
+
+    def epoch():
+        B.gcn_forward(m, True)
+        B.gcn_loss_acc(m, sync=False)
+        B.gcn_backward(m)
+        B.gcn_sgd_step(m, wl.lr)
+
+    for _ in range(args.warmup):
+        epoch()
+    torch.cuda.synchronize()
+    B.gcn_timing_reset()
+    B.gcn_timing_enable(not args.no_kernel_timing)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(args.steps):
+        epoch()
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    B.gcn_timing_enable(False)
+    ev_ms = start.elapsed_time(stop)
+
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        B.gcn_calibration_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # final state, read after the timed region
+    B.gcn_forward(m, False)
+    loss, acc = B.gcn_loss_acc(m)
+
+    E, n = info["nnz"], info["n"]
+    widths = sorted(set(wl.dims[1:]), reverse=True)
+    spmm = {}
+    for w in widths:
+        cnt, ms = B.gcn_timing_read(w)
+        if cnt:
+            avg = ms / cnt
+            by = gather_bytes(E, n, w)
+            spmm["w%d" % w] = {"launches": cnt, "avg_ms": round(avg, 5), "gather_GBps": round(by / avg / 1e6, 1),
+                               "alu_frac_fp32": round(2.0 * E * w / (avg * 1e-3) / (FP32_PEAK_TFLOPS * 1e12), 4)}
+    dom_w = wl.dims[1]
+    roofline = None
+    if "w%d" % dom_w in spmm:
+        avg = spmm["w%d" % dom_w]["avg_ms"]
+        achieved = gather_bytes(E, n, dom_w) / avg / 1e6
+        roofline = {"bound": "hbm", "kernel": "aggregation (k_spmm_wave + k_spmm_group), width %d" % dom_w,
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name, dom_w),
+                    "bytes_per_launch": gather_bytes(E, n, dom_w), "avg_launch_ms": avg}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gcn_oracle as O
+        O.lib()
+        og = O.canonicalise(wl.n, wl.rowptr, wl.col)
+        ws = [w.astype(np.float64) for w in wl.weights]
+        x64 = wl.x.astype(np.float64)
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        n_ep, dt = 0, 0.0
+        t0 = time.perf_counter()
+        while n_ep < 1 or (dt * cores < 15.0 and n_ep < 5):      # about 15-30 s of CPU work, at most 5 epochs
+            ws, _ = O.train_epoch(og, x64, ws, wl.labels, wl.mask, wl.lr)
+            n_ep += 1
+            dt = time.perf_counter() - t0
+        cpu = {"value": round(n_ep / dt, 4), "unit": "epochs/s", "cores": cores, "kind": "oracle",
+               "sample": "%d full epoch(s) of %s (fp64 plain loops, OpenMP over rows) in %.1f s wall"
+                         % (n_ep, wl.name, dt)}
+
+    secs = max(wall, ev_ms / 1e3)
+    out = {
+        "metric": "GCN train epochs/sec (fwd+bwd) on one partition; SpMM HBM GB/s vs peak",
+        "value": round(args.steps / secs, 3), "unit": "epochs/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(1e3 * secs / args.steps, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n": n, "n_local": wl.n_local, "nnz_A_plus_I": E, "dims": wl.dims,
+                   "lr": wl.lr, "optimizer": "sgd", "seed": args.seed},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "spmm": spmm, "final_loss": round(loss, 6), "final_acc": round(acc, 6),
+        "event_ms_total": round(ev_ms, 3), "wall_s_total": round(wall, 4),
+        "graph_create_s": round(t_create, 3), "generate_s": round(t_gen, 1),
+        "workspace_bytes": int(g.ws.numel() + m.ws.numel()),
+        "paper_context": "paper: about 1 s per epoch, Reddit (avg degree 100), 5 x GTX 1080 Ti (Section 1)",
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

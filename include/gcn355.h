@@ -150,6 +150,16 @@ int gcn_timing_enable(int on);
 int gcn_timing_reset(void);
 int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
 
+/* Benchmark sweeps: sets a named integer knob that selects among equivalent kernel variants or launch
+ * shapes (e.g. "spmm_variant").  Results do not depend on any knob beyond rounding order.  Unknown names
+ * are stored and ignored. */
+int gcn_set_tunable(const char *name, int64_t value);
+
+/* Measurement aid: copies `bytes` (a multiple of 16) from src to dst [dev] with one plain streaming
+ * kernel (k_calibration_copy), which reads and writes exactly `bytes` each.  Hardware byte counters
+ * collected for the library's kernels are scaled by what they report for this one.  Asynchronous. */
+int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

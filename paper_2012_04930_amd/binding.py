@@ -26,6 +26,7 @@ EXPORTS = [
     "gcn_graph_get_csr", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
+    "gcn_calibration_copy", "gcn_set_tunable",
 ]
 
 _lib = None
@@ -70,6 +71,8 @@ def lib():
         L.gcn_timing_enable.argtypes = [C.c_int]
         L.gcn_timing_reset.argtypes = []
         L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
+        L.gcn_calibration_copy.argtypes = [vp, vp, sz, vp]
+        L.gcn_set_tunable.argtypes = [C.c_char_p, i64]
         for name in EXPORTS:
             if name != "gcn_last_error":
                 getattr(L, name).restype = C.c_int
@@ -246,3 +249,13 @@ def gcn_timing_read(width: int):
     cnt, ms = C.c_int64(), C.c_double()
     _check(lib().gcn_timing_read(width, C.byref(cnt), C.byref(ms)))
     return cnt.value, ms.value
+
+
+def gcn_calibration_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().gcn_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()))
+
+
+def gcn_set_tunable(name: str, value: int) -> None:
+    _check(lib().gcn_set_tunable(name.encode(), value))

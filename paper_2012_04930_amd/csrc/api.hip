@@ -5,6 +5,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <string>
 
 #include "common.hpp"
 
@@ -17,6 +18,19 @@ void set_error(const char *fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+// ------------------------------------------------------------------------------------------- tunables
+namespace {
+std::mutex g_knob_mutex;
+std::vector<std::pair<std::string, int64_t>> g_knobs;
+}  // namespace
+
+int64_t tunable(const char *name, int64_t fallback) {
+    std::lock_guard<std::mutex> lk(g_knob_mutex);
+    for (auto &k : g_knobs)
+        if (k.first == name) return k.second;
+    return fallback;
 }
 
 // ------------------------------------------------------------------------------------------- timing
@@ -67,7 +81,7 @@ using namespace gcn;
 
 // ------------------------------------------------------------------------------------------- objects
 struct gcn_graph {
-    int64_t n = 0, nnz_in = 0, E = 0, E_p = 0, n_train = 0;
+    int64_t n = 0, nnz_in = 0, E = 0, n_heavy = 0, n_train = 0;
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;
     PrepBuffers pb{};
@@ -116,14 +130,13 @@ bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 void carve_graph(Carver &c, gcn_graph &g) {
     const int64_t n = g.n, cap = g.nnz_in + n;
     g.pb.rowptr = c.take<int64_t>(n + 1);
-    g.pb.col = c.take<int32_t>(cap);
+    g.pb.col = c.take<int32_t>(cap + kColSlack);
     g.pb.deg = c.take<int32_t>(n);
     g.pb.dinv = c.take<float>(n);
-    g.pb.rowptr_p = c.take<int64_t>(n + 1);
-    g.pb.col_p = c.take<int32_t>(cap + n * (kRowPad - 1));
     g.pb.perm = c.take<int32_t>(n);
     g.pb.scratch = c.take<int32_t>(cap);
-    g.pb.plen = c.take<int32_t>(n);
+    g.pb.heavy = c.take<int32_t>(n);
+    g.pb.hpos = c.take<int64_t>(n + 1);
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
     g.pb.flags = c.take<int32_t>(16);
     g.x = c.take<float>((size_t)(n + 1) * g.ldf);
@@ -263,10 +276,9 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     FAIL_IF(prep_schedule(n, g->pb, st));
     FAIL_IF(pad_rows_f32(feat, n, f, g->x, g->ldf, nullptr, st));
     FAIL_IF(fill_zero(g->x + (size_t)n * g->ldf, (size_t)g->ldf * sizeof(float), st));
-    int64_t ends[2];
+    int64_t ends[1];
     HIP_OR_FAIL(hipMemcpyAsync(flags, g->pb.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
     HIP_OR_FAIL(hipMemcpyAsync(&ends[0], g->pb.rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    HIP_OR_FAIL(hipMemcpyAsync(&ends[1], g->pb.rowptr_p + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     HIP_OR_FAIL(hipStreamSynchronize(st));
     if (flags[0] & 4) {
         set_error("gcn_graph_create: the adjacency pattern is not symmetric");
@@ -274,7 +286,7 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         return GCN_EGRAPH;
     }
     g->E = ends[0];
-    g->E_p = ends[1];
+    g->n_heavy = flags[4];
     g->max_deg = flags[3];
 #undef FAIL_IF
 #undef HIP_OR_FAIL
@@ -347,7 +359,7 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     if (rc) return rc;
     rc = fill_zero(t + (size_t)g->n * ld, (size_t)ld * sizeof(float), st);
     if (rc) return rc;
-    SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, t, ld, z, ld, width, kEpiNone, 0u, 1.0f, 0ull};
+    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, ld, z, ld, width, kEpiNone, 0u, 1.0f, 0ull};
     rc = spmm_launch(a, st);
     if (rc) return rc;
     return unpad_rows_f32(z, ld, g->n, width, out, nullptr, st);
@@ -508,7 +520,7 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
         int rc = gemm_nn(h_prev, ld_prev, ly.w, ly.ld_out, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out, g->pb.dinv, st);
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]
-        SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, ly.t, ly.ld_out, ly.h, ly.ld_out,
+        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.t, ly.ld_out, ly.h, ly.ld_out,
                    ly.d_out, l < m->L ? kEpiRelu : kEpiNone, 0u, 1.0f, 0ull};
         if (l < m->L && training && m->p > 0.0f) {
             a.drop_threshold = (uint32_t)std::floor((double)m->p * 4294967296.0);
@@ -574,7 +586,7 @@ int gcn_backward(gcn_model *m, void *stream) {
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
-        SpmmArgs a{g->pb.rowptr_p, g->pb.col_p, g->pb.perm, g->pb.dinv, g->n, ly.dzs, ly.ld_out, ly.g, ly.ld_out,
+        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.dzs, ly.ld_out, ly.g, ly.ld_out,
                    ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
         int rc = spmm_launch(a, st);
         if (rc) return rc;
@@ -611,6 +623,29 @@ int gcn_sgd_step(gcn_model *m, float lr, void *stream) {
 }
 
 // ------------------------------------------------------------------------------------------- timing
+int gcn_set_tunable(const char *name, int64_t value) {
+    if (!name) {
+        set_error("gcn_set_tunable: null name");
+        return GCN_EINVAL;
+    }
+    std::lock_guard<std::mutex> lk(g_knob_mutex);
+    for (auto &k : g_knobs)
+        if (k.first == name) {
+            k.second = value;
+            return GCN_OK;
+        }
+    g_knobs.push_back({std::string(name), value});
+    return GCN_OK;
+}
+
+int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (!src || !dst) {
+        set_error("gcn_calibration_copy: null pointer");
+        return GCN_EINVAL;
+    }
+    return calibration_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 int gcn_timing_enable(int on) {
     std::lock_guard<std::mutex> lk(g_tmutex);
     g_timing = on != 0;

@@ -14,6 +14,9 @@ namespace gcn {
 
 void set_error(const char *fmt, ...);
 
+// Named integer knobs for benchmark sweeps (gcn_set_tunable); unknown names read as the default.
+int64_t tunable(const char *name, int64_t fallback);
+
 #define GCN_HIP(call)                                                                          \
     do {                                                                                       \
         hipError_t e_ = (call);                                                                \
@@ -34,7 +37,8 @@ void set_error(const char *fmt, ...);
 
 constexpr int kWave = 64;
 constexpr int kLdAlign = 16;   // leading dimensions are multiples of 16 elements (64 B in fp32)
-constexpr int kRowPad = 8;     // scheduled rows are padded to a multiple of 8 entries
+constexpr int kColSlack = 64;  // readable entries after the last column index (index prefetch runs one step ahead)
+constexpr int kHeavyDegree = 32;  // rows with at least this many entries get a whole wave in the aggregation
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -63,15 +67,14 @@ struct PrepBuffers {
     int32_t *col;      // <= nnz_in + n
     int32_t *deg;      // n
     float *dinv;       // n
-    // schedule: rows in processing order, each padded to a multiple of kRowPad with column n
-    int64_t *rowptr_p; // n + 1
-    int32_t *col_p;    // <= nnz_in + n + n * (kRowPad - 1)
+    // schedule: heavy rows (degree >= kHeavyDegree) first, then light rows, each in ascending vertex order
     int32_t *perm;     // n   slot -> row
     // scratch
     int32_t *scratch;  // nnz_in + n
-    int32_t *plen;     // n
+    int32_t *heavy;    // n   1 if the row is heavy
+    int64_t *hpos;     // n + 1   exclusive prefix of heavy[]
     int64_t *blocksum; // scan partials
-    int32_t *flags;    // 16 ints: [0] graph error, [1] label error, [2] n_train, [3] max degree
+    int32_t *flags;    // 16 ints: [0] graph error, [1] label error, [2] n_train, [3] max degree, [4] heavy rows
 };
 
 int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, int32_t *flags,
@@ -95,17 +98,21 @@ int loss_forward(int64_t n, int classes, const float *logits, int ld, const int3
                  const float *dinv, int64_t n_train, float *dzs, int ld_dz, double *loss_part, long long *corr_part,
                  float *result /* [0] loss, [1] accuracy, as float */, long long *result_correct, hipStream_t st);
 int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st);
+int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
-// Aggregation (spmm.hip):  out[r, :] = dinv[r] * sum over the scheduled row of r of  t[col, :],
-// where t already carries the factor dinv[col] and has an all-zero row n for the padding entries.
+// Aggregation (spmm.hip):  out[r, :] = dinv[r] * sum over the columns c of row r of  t[c, :],
+// where t already carries the factor dinv[c] and has an all-zero row n that stands in for entries
+// past the end of a row.  Rows are taken in schedule order: perm[0 .. n_heavy) one wave each, the rest
+// one lane group each.
 enum SpmmEpilogue { kEpiNone = 0, kEpiRelu = 1 };
 struct SpmmArgs {
-    const int64_t *rowptr_p;
-    const int32_t *col_p;
+    const int64_t *rowptr;
+    const int32_t *col;     // kColSlack readable entries follow the last one
     const int32_t *perm;
     const float *dinv;
     int64_t n;
+    int64_t n_heavy;
     const float *t;
     int ld_t;
     float *out;

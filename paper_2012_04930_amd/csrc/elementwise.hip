@@ -143,6 +143,12 @@ __global__ __launch_bounds__(kThreads) void k_loss_final(int parts, const double
     }
 }
 
+// Plain streaming copy of 16-byte words: the known-size kernel hardware byte counters are scaled by.
+__global__ void k_calibration_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t words) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < words) dst[t] = src[t];
+}
+
 __global__ void k_sgd(float *__restrict__ w, const float *__restrict__ dw, size_t count, float lr) {
     size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < count) w[t] = w[t] - lr * dw[t];
@@ -194,6 +200,18 @@ int loss_forward(int64_t n, int classes, const float *logits, int ld, const int3
     GCN_LAUNCH_CHECK();
     k_loss_final<<<dim3(1), dim3(kThreads), 0, st>>>(blocks, loss_part, corr_part, 1.0 / (double)n_train, result,
                                                      result_correct);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+    if (bytes % 16 != 0 || bytes == 0 || bytes / 16 > 0x7fffffffull * 256ull) {
+        set_error("calibration copy: size must be a positive multiple of 16 bytes");
+        return GCN_EINVAL;
+    }
+    const size_t words = bytes / 16;
+    k_calibration_copy<<<dim3((unsigned)((words + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+        (const uint4 *)src, (uint4 *)dst, words);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -259,30 +259,20 @@ __global__ void k_dinv(int64_t n, const int32_t *__restrict__ deg, float *__rest
 }
 
 // --------------------------------------------------------------------------------------------- schedule
-__global__ void k_padded_len(int64_t n, const int32_t *__restrict__ perm, const int32_t *__restrict__ deg,
-                             int32_t *__restrict__ plen) {
-    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (s < n) plen[s] = (deg[perm[s]] + kRowPad - 1) / kRowPad * kRowPad;
+__global__ void k_flag_heavy(int64_t n, const int32_t *__restrict__ deg, int32_t *__restrict__ heavy) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) heavy[i] = deg[i] >= kHeavyDegree ? 1 : 0;
 }
 
-__global__ void k_identity(int64_t n, int32_t *__restrict__ perm) {
-    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (s < n) perm[s] = (int32_t)s;
-}
-
-// One wave per slot: the row's columns, then column n (the all-zero row) up to the padded length.
-__global__ __launch_bounds__(kThreads) void k_fill_padded(int64_t n, const int32_t *__restrict__ perm,
-                                                          const int64_t *__restrict__ rowptr,
-                                                          const int32_t *__restrict__ col,
-                                                          const int64_t *__restrict__ rowptr_p,
-                                                          int32_t *__restrict__ col_p) {
-    int64_t s = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (s >= n) return;
-    int lane = threadIdx.x & 63;
-    int r = perm[s];
-    int64_t src = rowptr[r], d = rowptr[r + 1] - src;
-    int64_t dst = rowptr_p[s], dp = rowptr_p[s + 1] - dst;
-    for (int64_t t = lane; t < dp; t += 64) col_p[dst + t] = t < d ? col[src + t] : (int32_t)n;
+// Stable two-way partition: heavy rows keep their order in slots [0, n_heavy), light rows theirs after.
+__global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const int64_t *__restrict__ hpos,
+                             int32_t *__restrict__ perm, int32_t *flags) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t n_heavy = hpos[n];
+    const int64_t slot = heavy[i] ? hpos[i] : n_heavy + (i - hpos[i]);
+    perm[slot] = (int32_t)i;
+    if (i == 0) flags[4] = (int32_t)n_heavy;
 }
 
 __global__ void k_labels_mask(int64_t n, const int32_t *__restrict__ labels, const uint8_t *__restrict__ mask,
@@ -336,14 +326,11 @@ int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32
 }
 
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
-    k_identity<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.perm);
+    k_flag_heavy<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.deg, pb.heavy);
     GCN_LAUNCH_CHECK();
-    k_padded_len<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.perm, pb.deg, pb.plen);
-    GCN_LAUNCH_CHECK();
-    int rc = exclusive_scan(n, pb.plen, pb.rowptr_p, pb.blocksum, st);
+    int rc = exclusive_scan(n, pb.heavy, pb.hpos, pb.blocksum, st);
     if (rc) return rc;
-    k_fill_padded<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.perm, pb.rowptr, pb.col,
-                                                                                  pb.rowptr_p, pb.col_p);
+    k_place_rows<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.heavy, pb.hpos, pb.perm, pb.flags);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -3,14 +3,18 @@
 //
 // The factor d_j^-1/2 of A_hat_ij = d_i^-1/2 d_j^-1/2 is already folded into the rows of the input
 // (its producer scales row j once), so a row of the output is a plain sum of gathered input rows
-// times d_i^-1/2.  No value array is read: 4 bytes of column index per nonzero.  Rows are walked in
-// schedule order; each scheduled row is padded to a multiple of kRowPad entries with column n, an
-// all-zero input row, so the inner loop has no tail.
+// times d_i^-1/2.  No value array is read: 4 bytes of column index per nonzero.  Entries past the
+// end of a row are replaced by column n, an all-zero input row, so inner loops need no lane masks.
 //
-// Work split: a group of LPR lanes owns one output row; each lane carries one float4 of the row
-// (LPR * 4 >= leading dimension).  A wave therefore works on 64 / LPR rows at once.  Column indices
-// are fetched LPR at a time, one per lane (coalesced), and handed round the group by cross-lane
-// reads; feature rows are fetched as 16-byte loads, a whole row per group per load instruction.
+// A group of LPR lanes covers one input row with one 16-byte load per lane (LPR * 4 >= leading
+// dimension), so every load instruction moves whole rows, contiguous in memory.
+//   heavy rows (degree >= kHeavyDegree): one wave per output row; its 64 / LPR lane groups take
+//     interleaved neighbours, column indices are wave-uniform and travel through the scalar path;
+//     the groups' partial sums meet in a cross-lane reduction at the end.
+//   light rows: one lane group per output row (64 / LPR rows per wave); each lane fetches one column
+//     index (coalesced) and the group hands them round with cross-lane reads.
+// Workgroup ids are dealt round-robin over the XCDs, so block ids are remapped to give each XCD one
+// contiguous range of rows: neighbouring rows share neighbours, and each XCD has its own L2.
 #include "common.hpp"
 
 namespace gcn {
@@ -46,79 +50,222 @@ __device__ inline float finish(float v, const Epi &ep, int64_t row, int c) {
     return v;
 }
 
-template <int LPR, int U>
-__global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restrict__ rowptr_p,
-                                                         const int32_t *__restrict__ col_p,
+__device__ inline void store_row_piece(float *__restrict__ out, int ld_out, int r, int sub, float4 a, float d,
+                                       const Epi &ep) {
+    const int c0 = sub * 4;
+    float4 o;
+    o.x = finish(a.x * d, ep, r, c0 + 0);
+    o.y = finish(a.y * d, ep, r, c0 + 1);
+    o.z = finish(a.z * d, ep, r, c0 + 2);
+    o.w = finish(a.w * d, ep, r, c0 + 3);
+    reinterpret_cast<float4 *>(out + (int64_t)r * ld_out)[sub] = o;
+}
+
+// One 16-byte piece of input row c: byte offset c * row_bytes + lane_bytes from t.  With NARROW the
+// whole input is below 4 GiB and the offset is formed in 32 bits (scalar base + 32-bit lane offset).
+template <bool NARROW>
+__device__ inline float4 load_piece(const float *__restrict__ t, int c, uint32_t row_bytes, uint32_t lane_bytes) {
+    if (NARROW) {
+        const uint32_t off = (uint32_t)c * row_bytes + lane_bytes;
+        return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(t) + off);
+    } else {
+        const uint64_t off = (uint64_t)(uint32_t)c * row_bytes + lane_bytes;
+        return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(t) + off);
+    }
+}
+
+__device__ inline void add4(float4 &a, const float4 &v) {
+    a.x += v.x;
+    a.y += v.y;
+    a.z += v.z;
+    a.w += v.w;
+}
+
+// block id -> position in the row range, so that XCD x (block ids congruent x mod 8) walks one
+// contiguous eighth of the range
+__device__ inline int xcd_contiguous_block(int nblocks) {
+    const int per_xcd = (nblocks + kXcds - 1) / kXcds;
+    return (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+}
+
+// ------------------------------------------------------------------------------------------------ heavy rows
+template <int LPR, int U, bool NARROW>
+__global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ col,
+                                                        const int32_t *__restrict__ perm,
+                                                        const float *__restrict__ dinv, int zero_row,
+                                                        int64_t n_rows, const float *__restrict__ t, int ld_t,
+                                                        float *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+    constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
+    constexpr int STEP = GPW * U;      // neighbours per unrolled step
+    static_assert(STEP <= kColSlack, "the index prefetch may run one step past the end of col");
+    constexpr int RPB = kThreads / 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = lane / LPR, sub = lane % LPR;
+    const int blk = xcd_contiguous_block(nblocks);
+    if (blk >= nblocks) return;
+    const int64_t s = (int64_t)blk * RPB + wave;
+    if (s >= n_rows) return;
+    const int r = perm[s];
+    const int64_t beg = rowptr[r], end = rowptr[r + 1];
+    // lanes beyond the row's width re-read its first piece (in bounds, same cache line) and store nothing
+    const uint32_t lane_bytes = (sub * 4 < ld_t) ? sub * 16u : 0u;
+    const uint32_t row_bytes = (uint32_t)ld_t * 4u;
+
+    // group g takes entries e + u * GPW + g, u = 0..U-1; all addresses are wave-uniform
+    auto fetch_indices = [&](int (&c)[U], int64_t e) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (GPW == 1) {
+                c[u] = col[e + u];
+            } else if (GPW == 2) {
+                const int c0 = col[e + 2 * u], c1 = col[e + 2 * u + 1];
+                c[u] = grp ? c1 : c0;
+            } else {
+                c[u] = col[e + u * GPW + grp];
+            }
+        }
+    };
+
+    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int64_t full_end = beg + (end - beg) / STEP * STEP;
+    int c[U];
+    fetch_indices(c, beg);            // may read up to STEP entries past `end`: inside col + slack
+    for (int64_t e = beg; e < full_end; e += STEP) {
+        int cn[U];
+        fetch_indices(cn, e + STEP);
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = load_piece<NARROW>(t, c[u], row_bytes, lane_bytes);
+#pragma unroll
+        for (int u = 0; u < U; u += 2) {
+            add4(acc0, v[u]);
+            add4(acc1, v[u + 1]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) c[u] = cn[u];
+    }
+    if (full_end < end) {
+        // last partial step: entries at or past `end` become the all-zero row
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t pos = full_end + u * GPW + grp;
+            const int cc = pos < end ? c[u] : zero_row;
+            v[u] = load_piece<NARROW>(t, cc, row_bytes, lane_bytes);
+        }
+#pragma unroll
+        for (int u = 0; u < U; u += 2) {
+            add4(acc0, v[u]);
+            add4(acc1, v[u + 1]);
+        }
+    }
+    float4 a4 = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
+#pragma unroll
+    for (int d = LPR; d < 64; d <<= 1) {
+        a4.x += __shfl_xor(a4.x, d, 64);
+        a4.y += __shfl_xor(a4.y, d, 64);
+        a4.z += __shfl_xor(a4.z, d, 64);
+        a4.w += __shfl_xor(a4.w, d, 64);
+    }
+    if (grp == 0 && sub * 4 < ld_out) store_row_piece(out, ld_out, r, sub, a4, dinv[r], ep);
+}
+
+// ------------------------------------------------------------------------------------------------ light rows
+template <int LPR, int U, bool NARROW>
+__global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restrict__ rowptr,
+                                                         const int32_t *__restrict__ col,
                                                          const int32_t *__restrict__ perm,
-                                                         const float *__restrict__ dinv, int64_t n,
-                                                         const float *__restrict__ t, int ld_t,
+                                                         const float *__restrict__ dinv, int zero_row,
+                                                         int64_t n_rows, const float *__restrict__ t, int ld_t,
                                                          float *__restrict__ out, int ld_out, int nblocks, Epi ep) {
-    static_assert(kRowPad % U == 0, "rows are padded to a multiple of the unroll");
     static_assert(LPR % U == 0, "one index fetch feeds a whole number of unrolled steps");
     constexpr int GPW = 64 / LPR;                 // rows per wave
     constexpr int RPB = (kThreads / 64) * GPW;    // rows per workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, sub = lane % LPR;
-    // consecutive workgroup ids land on different XCDs; give each XCD one contiguous range of rows
-    const int per_xcd = (nblocks + kXcds - 1) / kXcds;
-    const int blk = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    const int blk = xcd_contiguous_block(nblocks);
     if (blk >= nblocks) return;
     const int64_t s = (int64_t)blk * RPB + wave * GPW + grp;
-    const bool live = s < n;
-    const bool lane_on = sub * 4 < ld_t;
+    const bool live = s < n_rows;
+    const uint32_t lane_bytes = (sub * 4 < ld_t) ? sub * 16u : 0u;
+    const uint32_t row_bytes = (uint32_t)ld_t * 4u;
     int64_t beg = 0, end = 0;
     int r = 0;
     if (live) {
-        beg = rowptr_p[s];
-        end = rowptr_p[s + 1];
         r = perm[s];
+        beg = rowptr[r];
+        end = rowptr[r + 1];
     }
-    const float4 *tv = reinterpret_cast<const float4 *>(t) + sub;
-    const int ld4 = ld_t >> 2;
     float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f);
     float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
-    int nxt = (beg + sub < end) ? col_p[beg + sub] : (int)n;
+    int nxt = (beg + sub < end) ? col[beg + sub] : zero_row;
     for (int64_t e = beg; e < end; e += LPR) {
-        const int mine = nxt;
+        const int mine = nxt;         // entry e + sub, or the zero row past the end
         const int cnt = (end - e) < LPR ? (int)(end - e) : LPR;
         const int64_t e2 = e + LPR + sub;
-        nxt = (e2 < end) ? col_p[e2] : (int)n;
+        nxt = (e2 < end) ? col[e2] : zero_row;
         for (int k = 0; k < cnt; k += U) {
             int c[U];
             float4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) c[u] = __shfl(mine, grp * LPR + k + u, 64);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                v[u] = lane_on ? tv[(int64_t)c[u] * ld4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int u = 0; u < U; ++u) v[u] = load_piece<NARROW>(t, c[u], row_bytes, lane_bytes);
+            if (U == 1) {
+                add4(acc0, v[0]);
+            } else {
 #pragma unroll
-            for (int u = 0; u < U; u += 2) {
-                acc0.x += v[u].x; acc0.y += v[u].y; acc0.z += v[u].z; acc0.w += v[u].w;
-                acc1.x += v[u + 1].x; acc1.y += v[u + 1].y; acc1.z += v[u + 1].z; acc1.w += v[u + 1].w;
+                for (int u = 0; u + 1 < U; u += 2) {
+                    add4(acc0, v[u]);
+                    add4(acc1, v[u + 1]);
+                }
             }
         }
     }
     if (live && sub * 4 < ld_out) {
-        const float d = dinv[r];
-        const int c0 = sub * 4;
-        float4 o;
-        o.x = finish((acc0.x + acc1.x) * d, ep, r, c0 + 0);
-        o.y = finish((acc0.y + acc1.y) * d, ep, r, c0 + 1);
-        o.z = finish((acc0.z + acc1.z) * d, ep, r, c0 + 2);
-        o.w = finish((acc0.w + acc1.w) * d, ep, r, c0 + 3);
-        reinterpret_cast<float4 *>(out + (int64_t)r * ld_out)[sub] = o;
+        float4 a4 = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
+        store_row_piece(out, ld_out, r, sub, a4, dinv[r], ep);
     }
 }
 
-template <int LPR>
-int launch_group(const SpmmArgs &a, hipStream_t st) {
-    constexpr int RPB = (kThreads / 64) * (64 / LPR);
-    const int nblocks = (int)((a.n + RPB - 1) / RPB);
-    const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
+// true when every byte of the input (n + 1 rows) is addressable with a 32-bit offset
+inline bool narrow_ok(const SpmmArgs &a) { return (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * 4ull <= 0xffffffffull; }
+
+template <int LPR, int UW, int UG>
+int launch(const SpmmArgs &a, hipStream_t st) {
     Epi ep{a.epilogue, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
-    k_spmm_group<LPR, (LPR < 8 ? LPR : 8)><<<dim3(grid), dim3(kThreads), 0, st>>>(a.rowptr_p, a.col_p, a.perm, a.dinv, a.n, a.t,
-                                                                 a.ld_t, a.out, a.ld_out, nblocks, ep);
-    GCN_LAUNCH_CHECK();
+    const bool narrow = narrow_ok(a);
+    const int zero_row = (int)a.n;
+    if (a.n_heavy > 0) {
+        constexpr int RPB = kThreads / 64;
+        const int nblocks = (int)((a.n_heavy + RPB - 1) / RPB);
+        const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
+        if (narrow)
+            k_spmm_wave<LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, a.t, a.ld_t, a.out, a.ld_out, nblocks, ep);
+        else
+            k_spmm_wave<LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, a.t, a.ld_t, a.out, a.ld_out, nblocks, ep);
+        GCN_LAUNCH_CHECK();
+    }
+    const int64_t n_light = a.n - a.n_heavy;
+    if (n_light > 0) {
+        constexpr int RPB = (kThreads / 64) * (64 / LPR);
+        const int nblocks = (int)((n_light + RPB - 1) / RPB);
+        const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
+        if (narrow)
+            k_spmm_group<LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, a.t, a.ld_t, a.out, a.ld_out, nblocks,
+                ep);
+        else
+            k_spmm_group<LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, a.t, a.ld_t, a.out, a.ld_out, nblocks,
+                ep);
+        GCN_LAUNCH_CHECK();
+    }
     return GCN_OK;
 }
 
@@ -126,18 +273,20 @@ int launch_group(const SpmmArgs &a, hipStream_t st) {
 
 int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     if (a.n <= 0) return GCN_OK;
-    if (a.ld_t % 4 != 0 || a.ld_out % 4 != 0 || a.ld_out > a.ld_t || a.ld_t > 256) {
-        set_error("aggregation: unsupported leading dimensions %d / %d", a.ld_t, a.ld_out);
+    if (a.ld_t % 4 != 0 || a.ld_out % 4 != 0 || a.ld_out > a.ld_t || a.ld_t > 256 || a.n_heavy < 0 ||
+        a.n_heavy > a.n) {
+        set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld)", a.ld_t, a.ld_out,
+                  (long long)a.n_heavy, (long long)a.n);
         return GCN_EINVAL;
     }
     timing_begin(a.width, st);
     int rc;
     const int vecs = a.ld_t / 4;
-    if (vecs <= 4) rc = launch_group<4>(a, st);
-    else if (vecs <= 8) rc = launch_group<8>(a, st);
-    else if (vecs <= 16) rc = launch_group<16>(a, st);
-    else if (vecs <= 32) rc = launch_group<32>(a, st);
-    else rc = launch_group<64>(a, st);
+    if (vecs <= 4) rc = launch<4, 2, 4>(a, st);
+    else if (vecs <= 8) rc = launch<8, 2, 8>(a, st);
+    else if (vecs <= 16) rc = launch<16, 4, 8>(a, st);
+    else if (vecs <= 32) rc = launch<32, 8, 8>(a, st);
+    else rc = launch<64, 8, 8>(a, st);
     timing_end(st);
     return rc;
 }

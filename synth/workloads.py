@@ -83,7 +83,7 @@ def chung_lu_mid(seed: int = 0, scale: float = 1.0) -> Workload:
 
 
 def reddit_partition(seed: int = 0, scale: float = 1.0, avg_degree: float = 490.0, extra_frac: float = 0.02,
-                     shuffle_ids: bool = False) -> Workload:
+                     shuffle_ids: bool = False, p_intra: float = 0.8, p_cut: float = 0.05) -> Workload:
     """Config 3: one partition of a Reddit-shaped graph plus boundary-approximation vertices.
 
     n_local vertices in 50 communities; 5 % of edge draws are cut edges whose far end is
@@ -95,8 +95,8 @@ def reddit_partition(seed: int = 0, scale: float = 1.0, avg_degree: float = 490.
     n_local = max(500, int(round(46_600 * scale)))
     n_extra = int(round(extra_frac * n_local))
     deg = avg_degree * min(1.0, max(scale, 0.05) ** 0.5) if scale < 1.0 else avg_degree
-    rowptr, col, comm = graphs.community_power_law(n_local, 50, deg, 2.5, seed, p_intra=0.8,
-                                                   n_extra=n_extra, p_cut=0.05)
+    rowptr, col, comm = graphs.community_power_law(n_local, 50, deg, 2.5, seed, p_intra=p_intra,
+                                                   n_extra=n_extra, p_cut=p_cut)
     n = n_local + n_extra
     dims = [602, 128, 41]
     x = np.empty((n, dims[0]), dtype=np.float32)
