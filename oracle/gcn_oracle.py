@@ -217,7 +217,10 @@ def forward(g: Graph, X, Ws, p: float = 0.0, training: bool = False, seed: int =
     return Trace(Ts, Zs, H, keeps)
 
 
-def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0) -> Trace:
+def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0, gate=None) -> Trace:
+    """gate: optional list of arrays, one per hidden layer; when given, the ReLU decision [Z_l > 0] is read
+    from gate[l-1] > 0 instead of this trace's own Z_l.  Parity tests pass the other implementation's
+    activations here so that both sides take that yes/no decision on the same numbers."""
     nl = len(Ws)
     tr.loss, tr.correct, tr.n_train, dZL = loss_acc(tr.Z[-1], labels, mask)
     tr.dZ = [None] * nl
@@ -230,7 +233,7 @@ def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0) -> Trace:
         tr.dW[l - 1] = matmul_tn(tr.H[l - 1], G)
         if l > 1:
             dH = matmul_nt(G, Ws[l - 1])
-            Zp = tr.Z[l - 2]
+            Zp = tr.Z[l - 2] if gate is None else _f64(gate[l - 2])
             keep = tr.keep[l - 2]
             dZ = np.empty_like(dH)
             lib().orc_relu_dropout_backward(dH.size, _p(Zp, C.c_double),

@@ -57,11 +57,30 @@ def gpu_epoch(B, g, wl, lr=None, dropout_p=0.0, seed=0, training=True, epochs_be
     return m, out
 
 
-def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True):
+def gate_check(gpu_h, tr, rtol=RTOL_F32):
+    """The ReLU gate [Z > 0] is a yes/no decided by floating point.  Where the GPU's fp32 activation and
+    the oracle's fp64 pre-activation disagree on it, the pre-activation must be within tolerance of 0."""
+    for l, h in enumerate(gpu_h):
+        z = tr.Z[l]
+        keep = tr.keep[l]
+        on_ref = z > 0 if keep is None else (z > 0) & (keep != 0)
+        differ = on_ref != (h > 0)
+        if differ.any():
+            rms = float(np.sqrt(np.mean(z * z)))
+            assert np.abs(z[differ]).max() <= rtol * rms, "gate of layer %d differs away from zero" % (l + 1)
+
+
+def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True, gpu=None):
+    """One oracle epoch.  With gpu given, the backward pass takes the ReLU decisions from the GPU's
+    activations (checked by gate_check to differ from the oracle's own only at pre-activations ~ 0)."""
     og = O.canonicalise(wl.n, wl.rowptr, wl.col)
     ws = [w.astype(np.float64) for w in wl.weights]
     tr = O.forward(og, wl.x, ws, p=dropout_p, training=training, seed=seed, epoch=0)
-    O.backward(og, tr, ws, wl.labels, wl.mask, p=dropout_p if training else 0.0)
+    gate = None
+    if gpu is not None:
+        gate_check(gpu["H"], tr)
+        gate = gpu["H"]
+    O.backward(og, tr, ws, wl.labels, wl.mask, p=dropout_p if training else 0.0, gate=gate)
     new = O.sgd(ws, tr.dW, wl.lr if lr is None else lr)
     return og, tr, new
 

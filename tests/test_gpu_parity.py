@@ -134,7 +134,7 @@ def test_tiny_config_full_step(B, oracle):
     wl = workloads.tiny()                              # config 1
     g = H.gpu_graph(B, wl)
     _, gpu = H.gpu_epoch(B, g, wl)
-    _, tr, new = H.oracle_epoch(oracle, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
@@ -146,7 +146,7 @@ def test_mid_configs_full_step(B, oracle, make):
     wl = make()
     g = H.gpu_graph(B, wl)
     _, gpu = H.gpu_epoch(B, g, wl)
-    _, tr, new = H.oracle_epoch(oracle, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
@@ -195,7 +195,7 @@ def test_dropout_mask_and_scaling(B, oracle):
     g = H.gpu_graph(B, wl)
     p, seed = 0.4, 12345
     _, gpu = H.gpu_epoch(B, g, wl, dropout_p=p, seed=seed, training=True)
-    _, tr, new = H.oracle_epoch(oracle, wl, dropout_p=p, seed=seed, training=True)
+    _, tr, new = H.oracle_epoch(oracle, wl, dropout_p=p, seed=seed, training=True, gpu=gpu)
     keep = oracle.dropout_keep(seed, 0, 1, wl.n, wl.dims[1], p)
     assert np.all(gpu["H"][0][keep == 0] == 0.0)                  # same mask, bit for bit
     H.compare_epoch(oracle, wl, gpu, tr, new)
@@ -203,3 +203,40 @@ def test_dropout_mask_and_scaling(B, oracle):
     _, gpu_eval = H.gpu_epoch(B, g, wl, dropout_p=p, seed=seed, training=False)
     _, tr_eval, _ = H.oracle_epoch(oracle, wl, dropout_p=p, seed=seed, training=False)
     H.assert_close(gpu_eval["logits"], tr_eval.Z[-1], what="eval logits")
+
+
+# ------------------------------------------------------------------ full sizes, in the launch configuration bench.py times
+def test_benchmark_config_c3_full_size(B, oracle):
+    wl = workloads.reddit_partition()                  # 47,532 vertices, 23.7 M nonzeros, 602 -> 128 -> 41
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    rowptr, col, deg, dinv = [t.cpu().numpy() for t in B.gcn_graph_get_csr(g)]
+    np.testing.assert_array_equal(rowptr, og.rowptr)
+    np.testing.assert_array_equal(col, og.col)
+    np.testing.assert_array_equal(deg, og.deg)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+def test_config_c2_full_size(B, oracle):
+    wl = workloads.chung_lu_mid()                      # 100,000 vertices, light and heavy rows mixed
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+@pytest.mark.timeout(900)
+def test_config_c4_full_reddit_shape(B, oracle):
+    wl = workloads.reddit_full()                       # 232,965 vertices, ~114 M nonzeros, rows up to ~10 k entries
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    rowptr, col, deg, _ = [t.cpu().numpy() for t in B.gcn_graph_get_csr(g)]
+    np.testing.assert_array_equal(rowptr, og.rowptr)
+    np.testing.assert_array_equal(col, og.col)
+    np.testing.assert_array_equal(deg, og.deg)
+    del rowptr, col, deg
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
