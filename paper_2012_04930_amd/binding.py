@@ -108,8 +108,8 @@ class Graph:
         self.handle, self.ws, self.n, self.f, self.n_classes = handle, ws, n, f, n_classes
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().gcn_graph_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gcn_graph_destroy(self.handle)
             self.handle = None
 
 
@@ -147,6 +147,7 @@ def gcn_graph_get_csr(g: Graph):
 
 
 def gcn_aggregate(g: Graph, x: torch.Tensor, dtype: int = GCN_F32, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """A_hat x; with dtype = GCN_BF16 the scaled input is stored as bfloat16 before the aggregation."""
     L = lib()
     assert x.shape[0] == g.n
     width = x.shape[1]
@@ -165,8 +166,8 @@ class Model:
         self.handle, self.ws, self.graph, self.dims = handle, ws, graph, list(dims)
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().gcn_model_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gcn_model_destroy(self.handle)
             self.handle = None
 
 

@@ -85,7 +85,7 @@ struct gcn_graph {
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;
     PrepBuffers pb{};
-    float *x = nullptr;          // (n + 1) x ldf, zero padded, last row zero
+    void *x = nullptr;           // (n + 1) x ldf elements of store_dtype, zero padded, last row zero
     int32_t *labels = nullptr;
     uint8_t *mask = nullptr;
 };
@@ -94,10 +94,13 @@ struct Layer {
     int d_in, d_out, ld_in, ld_out;
     float *w;    // ld_in x ld_out
     float *dw;   // ld_in x ld_out
-    float *t;    // (n + 1) x ld_out : D^-1/2 (H_{l-1} W_l), row n zero
-    float *h;    // n x ld_out : H_l (l < L) or the logits (l = L)
-    float *dzs;  // (n + 1) x ld_out : D^-1/2 dLoss/dZ_l, row n zero
-    float *g;    // n x ld_out : A_hat dLoss/dZ_l
+    // the next four hold the model's storage type (float or bfloat16); the logits are always float
+    void *t;     // (n + 1) x ld_out : D^-1/2 (H_{l-1} W_l), row n zero
+    void *h;     // n x ld_out : H_l (l < L) or the logits (l = L)
+    void *dzs;   // (n + 1) x ld_out : D^-1/2 dLoss/dZ_l, row n zero
+    void *g;     // n x ld_out : A_hat dLoss/dZ_l
+    void *wb;    // bfloat16 mode: W as bfloat16, ld_in x ld_out
+    void *wbt;   // bfloat16 mode: W^T as bfloat16, ld_out x ld_in
 };
 
 struct gcn_model {
@@ -139,7 +142,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.hpos = c.take<int64_t>(n + 1);
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
     g.pb.flags = c.take<int32_t>(16);
-    g.x = c.take<float>((size_t)(n + 1) * g.ldf);
+    g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
     g.labels = c.take<int32_t>(n);
     g.mask = c.take<uint8_t>(n);
 }
@@ -150,11 +153,19 @@ void carve_model(Carver &c, gcn_model &m) {
     for (auto &ly : m.layers) {
         ly.w = c.take<float>((size_t)ly.ld_in * ly.ld_out);
         ly.dw = c.take<float>((size_t)ly.ld_in * ly.ld_out);
-        ly.t = c.take<float>((size_t)(n + 1) * ly.ld_out);
-        ly.h = c.take<float>((size_t)(n + 1) * ly.ld_out);
-        ly.dzs = c.take<float>((size_t)(n + 1) * ly.ld_out);
-        ly.g = c.take<float>((size_t)(n + 1) * ly.ld_out);
-        size_t need = gemm_tn_partial_floats(n, ly.ld_in, ly.ld_out);
+        const size_t es = m.dtype == GCN_BF16 ? 2 : 4;
+        const size_t act = (size_t)(n + 1) * ly.ld_out;
+        ly.t = c.take<char>(act * es);
+        ly.h = c.take<char>(act * 4);          // float-sized even in bfloat16 mode: the last layer's logits are float
+        ly.dzs = c.take<char>(act * es);
+        ly.g = c.take<char>(act * es);
+        ly.wb = ly.wbt = nullptr;
+        if (m.dtype == GCN_BF16) {
+            ly.wb = c.take<char>((size_t)ly.ld_in * ly.ld_out * 2);
+            ly.wbt = c.take<char>((size_t)ly.ld_in * ly.ld_out * 2);
+        }
+        size_t need = m.dtype == GCN_BF16 ? gemm_bf16_tn_partial_floats(n, ly.ld_in, ly.ld_out)
+                                          : gemm_tn_partial_floats(n, ly.ld_in, ly.ld_out);
         if (need > pf) pf = need;
     }
     m.partial_floats = pf;
@@ -180,11 +191,13 @@ extern "C" {
 const char *gcn_last_error(void) { return g_err; }
 
 int gcn_graph_workspace_bytes(int64_t n, int64_t nnz_in, int32_t f, int store_dtype, size_t *bytes) {
-    if (!bytes || n <= 0 || n >= 0x7ffffff0 || nnz_in < 0 || f < 1 || store_dtype != GCN_F32) {
+    if (!bytes || n <= 0 || n >= 0x7ffffff0 || nnz_in < 0 || f < 1 ||
+        (store_dtype != GCN_F32 && store_dtype != GCN_BF16)) {
         set_error("gcn_graph_workspace_bytes: bad argument");
         return GCN_EINVAL;
     }
     gcn_graph g;
+    g.store_dtype = store_dtype;
     g.n = n;
     g.nnz_in = nnz_in;
     g.f = f;
@@ -203,10 +216,6 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     if (!out || !rowptr || (!col && nnz_in > 0) || !feat || !labels || !train_mask || n <= 0 || n >= 0x7ffffff0 ||
         nnz_in < 0 || f < 1 || n_classes < 1) {
         set_error("gcn_graph_create: null pointer or bad size");
-        return GCN_EINVAL;
-    }
-    if (store_dtype != GCN_F32) {
-        set_error("gcn_graph_create: only float32 storage is implemented");
         return GCN_EINVAL;
     }
     size_t need = 0;
@@ -229,7 +238,7 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     g->n_classes = n_classes;
     g->store_dtype = store_dtype;
     Carver c(workspace);
-    carve_graph(c, *g);
+    carve_graph(c, *g);   // uses store_dtype
     int32_t flags[16];
 
 #define FAIL_IF(expr)            \
@@ -274,8 +283,9 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
 
     FAIL_IF(prep_canonical(n, nnz_in, rowptr, col, g->pb, st));
     FAIL_IF(prep_schedule(n, g->pb, st));
-    FAIL_IF(pad_rows_f32(feat, n, f, g->x, g->ldf, nullptr, st));
-    FAIL_IF(fill_zero(g->x + (size_t)n * g->ldf, (size_t)g->ldf * sizeof(float), st));
+    const size_t x_es = store_dtype == GCN_BF16 ? 2 : 4;
+    FAIL_IF(pad_rows(feat, n, f, g->x, store_dtype, g->ldf, nullptr, st));
+    FAIL_IF(fill_zero((char *)g->x + (size_t)n * g->ldf * x_es, (size_t)g->ldf * x_es, st));
     int64_t ends[1];
     HIP_OR_FAIL(hipMemcpyAsync(flags, g->pb.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
     HIP_OR_FAIL(hipMemcpyAsync(&ends[0], g->pb.rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
@@ -325,7 +335,8 @@ int gcn_graph_get_csr(const gcn_graph *g, int64_t *rowptr, int32_t *col, int32_t
 }
 
 int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, size_t *bytes) {
-    if (!g || !bytes || width < 1 || width > 1024 || dtype != GCN_F32) {
+    if (!g || !bytes || width < 1 || (dtype != GCN_F32 && dtype != GCN_BF16) ||
+        width > (dtype == GCN_BF16 ? 512 : 256)) {
         set_error("gcn_aggregate_workspace_bytes: bad argument");
         return GCN_EINVAL;
     }
@@ -353,30 +364,33 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     hipStream_t st = (hipStream_t)stream;
     Carver c(workspace);
     const int ld = padded_width(width);
-    float *t = c.take<float>((size_t)(g->n + 1) * ld);
+    float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
     float *z = c.take<float>((size_t)(g->n + 1) * ld);
-    rc = pad_rows_f32(in, g->n, width, t, ld, g->pb.dinv, st);
+    const size_t es = dtype == GCN_BF16 ? 2 : 4;
+    rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);
     if (rc) return rc;
-    rc = fill_zero(t + (size_t)g->n * ld, (size_t)ld * sizeof(float), st);
+    rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
     if (rc) return rc;
-    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, ld, z, ld, width, kEpiNone, 0u, 1.0f, 0ull};
+    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, dtype, ld, z, GCN_F32, ld, width,
+               kEpiNone, 0u, 1.0f, 0ull};
     rc = spmm_launch(a, st);
     if (rc) return rc;
-    return unpad_rows_f32(z, ld, g->n, width, out, nullptr, st);
+    return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
 }
 
 // ------------------------------------------------------------------------------------------- model
 int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes) {
-    if (!g || !bytes || check_dims(n_layers, dims) || dtype != GCN_F32) {
+    if (!g || !bytes || check_dims(n_layers, dims) || (dtype != GCN_F32 && dtype != GCN_BF16)) {
         set_error("gcn_model_workspace_bytes: bad argument");
         return GCN_EINVAL;
     }
     gcn_model m;
     m.g = g;
+    m.dtype = dtype;
     m.L = n_layers;
     for (int l = 0; l < n_layers; ++l)
         m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
-                                 nullptr, nullptr, nullptr, nullptr, nullptr});
+                                 nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(nullptr);
     carve_model(c, m);
     *bytes = c.bytes();
@@ -390,8 +404,8 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
         set_error("gcn_model_create: null pointer or bad layer widths");
         return GCN_EINVAL;
     }
-    if (dtype != GCN_F32) {
-        set_error("gcn_model_create: only float32 is implemented");
+    if ((dtype != GCN_F32 && dtype != GCN_BF16) || dtype != g->store_dtype) {
+        set_error("gcn_model_create: dtype must be GCN_F32 or GCN_BF16 and equal to the graph's storage type");
         return GCN_EINVAL;
     }
     if (dims[0] != g->f || dims[n_layers] != g->n_classes) {
@@ -421,7 +435,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     m->seed = seed;
     for (int l = 0; l < n_layers; ++l)
         m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
-                                  nullptr, nullptr, nullptr, nullptr, nullptr});
+                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(workspace);
     carve_model(c, *m);
     // zero everything once: padding columns, the extra zero rows and the weights start at zero
@@ -452,13 +466,17 @@ int gcn_set_weights(gcn_model *m, const float *flat, int on_host, void *stream) 
             // stage through the (currently idle) gradient buffer, then spread into the padded layout
             GCN_HIP(hipMemcpyAsync(ly.dw, flat + off, cnt * sizeof(float), hipMemcpyHostToDevice, st));
             GCN_HIP(hipStreamSynchronize(st));
-            int rc = pad_rows_f32(ly.dw, ly.d_in, ly.d_out, ly.w, ly.ld_out, nullptr, st);
+            int rc = pad_rows(ly.dw, ly.d_in, ly.d_out, ly.w, GCN_F32, ly.ld_out, nullptr, st);
             if (rc) return rc;
             GCN_HIP(hipStreamSynchronize(st));
             rc = fill_zero(ly.dw, (size_t)ly.ld_in * ly.ld_out * sizeof(float), st);
             if (rc) return rc;
         } else {
-            int rc = pad_rows_f32(flat + off, ly.d_in, ly.d_out, ly.w, ly.ld_out, nullptr, st);
+            int rc = pad_rows(flat + off, ly.d_in, ly.d_out, ly.w, GCN_F32, ly.ld_out, nullptr, st);
+            if (rc) return rc;
+        }
+        if (m->dtype == GCN_BF16) {
+            int rc = weight_copies(ly.w, ly.ld_in, ly.ld_out, ly.wb, ly.wbt, ly.ld_in, st);
             if (rc) return rc;
         }
         off += cnt;
@@ -480,16 +498,17 @@ int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_fl
     }
     const Layer &ly = m->layers[layer - 1];
     const int64_t n = m->g->n;
-    const float *src = nullptr;
+    const void *src = nullptr;
+    int src_dtype = m->dtype;
     int ld = ly.ld_out, cols = ly.d_out;
     int64_t rows = n;
     const float *rowdiv = nullptr;
     bool ok = true;
     switch (which) {
-        case GCN_T_W: src = ly.w; rows = ly.d_in; break;
-        case GCN_T_DW: src = ly.dw; rows = ly.d_in; ok = m->have_backward; break;
+        case GCN_T_W: src = ly.w; src_dtype = GCN_F32; rows = ly.d_in; break;
+        case GCN_T_DW: src = ly.dw; src_dtype = GCN_F32; rows = ly.d_in; ok = m->have_backward; break;
         case GCN_T_H: src = ly.h; ok = m->have_forward && layer < m->L; break;
-        case GCN_T_LOGITS: src = ly.h; ok = m->have_forward; break;
+        case GCN_T_LOGITS: src = ly.h; src_dtype = GCN_F32; ok = m->have_forward; break;
         case GCN_T_G: src = ly.g; ok = m->have_backward; break;
         case GCN_T_DZ: src = ly.dzs; rowdiv = m->g->pb.dinv; ok = m->have_backward; break;
         default: ok = false;
@@ -502,7 +521,7 @@ int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_fl
         set_error("gcn_get_tensor: destination holds %zu floats, %zu needed", dst_floats, (size_t)rows * cols);
         return GCN_EINVAL;
     }
-    return unpad_rows_f32(src, ld, rows, cols, dst, rowdiv, st);
+    return unpad_rows(src, src_dtype, ld, rows, cols, dst, rowdiv, st);
 }
 
 int gcn_forward(gcn_model *m, int training, void *stream) {
@@ -512,16 +531,20 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
     }
     hipStream_t st = (hipStream_t)stream;
     const gcn_graph *g = m->g;
-    const float *h_prev = g->x;
+    const bool bf = m->dtype == GCN_BF16;
+    const void *h_prev = g->x;
     int ld_prev = g->ldf;
     for (int l = 1; l <= m->L; ++l) {
         Layer &ly = m->layers[l - 1];
         // T = D^-1/2 (H_{l-1} W_l)
-        int rc = gemm_nn(h_prev, ld_prev, ly.w, ly.ld_out, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out, g->pb.dinv, st);
+        int rc = bf ? gemm_bf16_nn(h_prev, ld_prev, ly.wbt, ly.ld_in, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
+                                   g->pb.dinv, st)
+                    : gemm_nn((const float *)h_prev, ld_prev, ly.w, ly.ld_out, (float *)ly.t, ly.ld_out, g->n, ly.ld_in,
+                              ly.ld_out, g->pb.dinv, st);
         if (rc) return rc;
-        // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]
-        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.t, ly.ld_out, ly.h, ly.ld_out,
-                   ly.d_out, l < m->L ? kEpiRelu : kEpiNone, 0u, 1.0f, 0ull};
+        // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
+        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.t, m->dtype, ly.ld_out, ly.h,
+                   l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.d_out, l < m->L ? kEpiRelu : kEpiNone, 0u, 1.0f, 0ull};
         if (l < m->L && training && m->p > 0.0f) {
             a.drop_threshold = (uint32_t)std::floor((double)m->p * 4294967296.0);
             a.keep_scale = (float)(1.0 / (1.0 - (double)m->p));
@@ -547,8 +570,8 @@ int gcn_loss_acc(gcn_model *m, float *loss, float *acc, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const gcn_graph *g = m->g;
     Layer &ly = m->layers[m->L - 1];
-    int rc = loss_forward(g->n, ly.d_out, ly.h, ly.ld_out, g->labels, g->mask, g->pb.dinv, g->n_train, ly.dzs,
-                          ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st);
+    int rc = loss_forward(g->n, ly.d_out, (const float *)ly.h, ly.ld_out, g->labels, g->mask, g->pb.dinv, g->n_train,
+                          ly.dzs, m->dtype, ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st);
     if (rc) return rc;
     m->have_loss = true;
     if (loss || acc) {
@@ -583,23 +606,34 @@ int gcn_backward(gcn_model *m, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const gcn_graph *g = m->g;
     const float keep_scale = m->trained_forward ? (float)(1.0 / (1.0 - (double)m->p)) : 1.0f;
+    const bool bf = m->dtype == GCN_BF16;
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
-        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.dzs, ly.ld_out, ly.g, ly.ld_out,
-                   ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
+        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.dzs, m->dtype, ly.ld_out, ly.g,
+                   m->dtype, ly.ld_out, ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G
-        const float *h_prev = l > 1 ? m->layers[l - 2].h : g->x;
-        rc = gemm_tn(h_prev, ly.ld_in, ly.g, ly.ld_out, ly.dw, ly.ld_out, g->n, ly.ld_in, ly.ld_out, m->partials,
-                     m->partial_floats, st);
+        const void *h_prev = l > 1 ? m->layers[l - 2].h : g->x;
+        if (bf) {
+            int splits = 0;
+            rc = gemm_bf16_tn_partials(h_prev, ly.ld_in, ly.g, ly.ld_out, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
+                                       m->partials, m->partial_floats, &splits, st);
+            if (rc) return rc;
+            rc = reduce_partials(m->partials, splits, (size_t)ly.ld_in * ly.ld_out, ly.dw, st);
+        } else {
+            rc = gemm_tn((const float *)h_prev, ly.ld_in, (const float *)ly.g, ly.ld_out, ly.dw, ly.ld_out, g->n,
+                         ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
+        }
         if (rc) return rc;
         if (l > 1) {
             // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
             Layer &lp = m->layers[l - 2];
-            rc = gemm_nt(ly.g, ly.ld_out, ly.w, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out, g->pb.dinv,
-                         lp.h, lp.ld_out, keep_scale, st);
+            rc = bf ? gemm_bf16_nt(ly.g, ly.ld_out, ly.wb, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out,
+                                   g->pb.dinv, lp.h, lp.ld_out, keep_scale, st)
+                    : gemm_nt((const float *)ly.g, ly.ld_out, ly.w, ly.ld_out, (float *)lp.dzs, lp.ld_out, g->n,
+                              ly.ld_out, lp.ld_out, g->pb.dinv, (const float *)lp.h, lp.ld_out, keep_scale, st);
             if (rc) return rc;
         }
     }
@@ -616,6 +650,10 @@ int gcn_sgd_step(gcn_model *m, float lr, void *stream) {
     for (auto &ly : m->layers) {
         int rc = sgd_update(ly.w, ly.dw, (size_t)ly.ld_in * ly.ld_out, lr, st);
         if (rc) return rc;
+        if (m->dtype == GCN_BF16) {
+            rc = weight_copies(ly.w, ly.ld_in, ly.ld_out, ly.wb, ly.wbt, ly.ld_in, st);
+            if (rc) return rc;
+        }
     }
     m->epoch += 1;
     m->have_forward = m->have_loss = m->have_backward = false;

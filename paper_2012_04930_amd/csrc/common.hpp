@@ -88,15 +88,21 @@ size_t scan_blocks(int64_t n);
 
 // ---------------------------------------------------------------------------------------------
 // Layout helpers (elementwise.hip).  "padded" = row-major with leading dimension ld >= width, pad zero.
-int pad_rows_f32(const float *src, int64_t rows, int width, float *dst, int ld, const float *rowscale, hipStream_t st);
-int unpad_rows_f32(const float *src, int ld, int64_t rows, int width, float *dst, const float *rowdiv, hipStream_t st);
+// dst / src element type is float (GCN_F32) or bfloat16 (GCN_BF16); the caller-side matrix is always float.
+int pad_rows(const float *src, int64_t rows, int width, void *dst, int dst_dtype, int ld, const float *rowscale,
+             hipStream_t st);
+int unpad_rows(const void *src, int src_dtype, int ld, int64_t rows, int width, float *dst, const float *rowdiv,
+               hipStream_t st);
+// bfloat16 copies of w [rows x ld]: same layout (wb) and transposed [ld x ld_t] (wbt)
+int weight_copies(const float *w, int rows, int ld, void *wb, void *wbt, int ld_t, hipStream_t st);
 int fill_zero(void *p, size_t bytes, hipStream_t st);
 
 // Loss / accuracy / dLoss/dlogits (scaled by dinv for the aggregation that follows).
 constexpr int kLossBlocks = 512;
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
-                 const float *dinv, int64_t n_train, float *dzs, int ld_dz, double *loss_part, long long *corr_part,
-                 float *result /* [0] loss, [1] accuracy, as float */, long long *result_correct, hipStream_t st);
+                 const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
+                 long long *corr_part, float *result /* [0] loss, [1] accuracy, as float */,
+                 long long *result_correct, hipStream_t st);
 int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st);
 int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 
@@ -113,9 +119,11 @@ struct SpmmArgs {
     const float *dinv;
     int64_t n;
     int64_t n_heavy;
-    const float *t;
+    const void *t;      // float or bfloat16, ld_t elements per row, n + 1 rows
+    int t_dtype;
     int ld_t;
-    float *out;
+    void *out;          // float or bfloat16 (bfloat16 only from a bfloat16 input)
+    int out_dtype;
     int ld_out;
     int width;          // true width (<= ld)
     int epilogue;
@@ -139,6 +147,18 @@ int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
 size_t gemm_tn_partial_floats(int64_t rows, int M, int N);
 int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t rows, int M, int N,
             float *partials, size_t partial_floats, hipStream_t st);
+
+int reduce_partials(const float *partials, int splits, size_t count, float *c, hipStream_t st);
+
+// bfloat16 operands, float32 accumulation (gemm_bf16.hip).  a, b, c, gate are bfloat16 matrices; bt / b hold the
+// second operand with the shared dimension contiguous: nn takes W^T [N x K], nt takes W [N x K].
+int gemm_bf16_nn(const void *a, int lda, const void *bt, int ldb, void *c, int ldc, int64_t M, int K, int N,
+                 const float *rowscale, hipStream_t st);
+int gemm_bf16_nt(const void *a, int lda, const void *b, int ldb, void *c, int ldc, int64_t M, int K, int N,
+                 const float *rowscale, const void *gate, int ldg, float scale, hipStream_t st);
+size_t gemm_bf16_tn_partial_floats(int64_t rows, int M, int N);
+int gemm_bf16_tn_partials(const void *a, int lda, const void *b, int ldb, int ldc, int64_t rows, int M, int N,
+                          float *partials, size_t partial_floats, int *splits_out, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
 // Event timing of aggregation launches (api.hip)

@@ -4,6 +4,7 @@
 // vertex (Section 2.2).  The paper does not print its loss; this is the softmax cross-entropy of
 // the cited Kipf-Welling model, averaged over the train mask.  Update: plain SGD.
 #include "common.hpp"
+#include "dtypes.hpp"
 
 namespace gcn {
 
@@ -11,7 +12,8 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__global__ void k_pad_rows(const float *__restrict__ src, int64_t rows, int width, float *__restrict__ dst, int ld,
+template <typename TDst>
+__global__ void k_pad_rows(const float *__restrict__ src, int64_t rows, int width, TDst *__restrict__ dst, int ld,
                            const float *__restrict__ rowscale) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = rows * ld;
@@ -20,17 +22,18 @@ __global__ void k_pad_rows(const float *__restrict__ src, int64_t rows, int widt
     int c = (int)(t - r * ld);
     float v = c < width ? src[r * width + c] : 0.0f;
     if (rowscale) v *= rowscale[r];
-    dst[t] = v;
+    dst[t] = narrow<TDst>(v);
 }
 
-__global__ void k_unpad_rows(const float *__restrict__ src, int ld, int64_t rows, int width, float *__restrict__ dst,
+template <typename TSrc>
+__global__ void k_unpad_rows(const TSrc *__restrict__ src, int ld, int64_t rows, int width, float *__restrict__ dst,
                              const float *__restrict__ rowdiv) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = rows * width;
     if (t >= total) return;
     int64_t r = t / width;
     int c = (int)(t - r * width);
-    float v = src[r * ld + c];
+    float v = widen(src[r * ld + c]);
     if (rowdiv) v /= rowdiv[r];
     dst[t] = v;
 }
@@ -43,10 +46,11 @@ __global__ void k_fill_zero(uint32_t *__restrict__ p, size_t words) {
 
 // One wave per vertex, waves stride over the vertices in a fixed pattern, so every partial sum
 // is made of the same terms in the same order on every run.
+template <typename TDz>
 __global__ __launch_bounds__(kThreads) void k_loss(int64_t n, int classes, const float *__restrict__ logits, int ld,
                                                    const int32_t *__restrict__ labels,
                                                    const uint8_t *__restrict__ mask, const float *__restrict__ dinv,
-                                                   float inv_ntrain, float *__restrict__ dzs, int ld_dz,
+                                                   float inv_ntrain, TDz *__restrict__ dzs, int ld_dz,
                                                    double *__restrict__ loss_part,
                                                    long long *__restrict__ corr_part) {
     __shared__ double s_loss[kThreads / 64];
@@ -57,9 +61,9 @@ __global__ __launch_bounds__(kThreads) void k_loss(int64_t n, int classes, const
     long long my_corr = 0;
     for (int64_t v = (int64_t)blockIdx.x * (kThreads / 64) + wave; v < n; v += waves_total) {
         const float *z = logits + v * ld;
-        float *g = dzs + v * ld_dz;
+        TDz *g = dzs + v * ld_dz;
         if (!mask[v]) {
-            for (int c = lane; c < classes; c += 64) g[c] = 0.0f;
+            for (int c = lane; c < classes; c += 64) g[c] = narrow<TDz>(0.0f);
             continue;
         }
         // maximum and its lowest index
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void k_loss(int64_t n, int classes, const
         const float scale = dinv[v] * inv_ntrain;
         for (int c = lane; c < classes; c += 64) {
             float p = expf(z[c] - lse);
-            g[c] = (p - (c == y ? 1.0f : 0.0f)) * scale;
+            g[c] = narrow<TDz>((p - (c == y ? 1.0f : 0.0f)) * scale);
         }
         if (lane == 0) {
             my_loss += (double)(lse - z[y]);
@@ -154,23 +158,48 @@ __global__ void k_sgd(float *__restrict__ w, const float *__restrict__ dw, size_
     if (t < count) w[t] = w[t] - lr * dw[t];
 }
 
+// bfloat16 copies of a weight matrix w [rows x ld]: wb in the same layout, wbt transposed [ld x ld_t]
+__global__ void k_weight_copies(const float *__restrict__ w, int rows, int ld, bf16_t *__restrict__ wb,
+                                bf16_t *__restrict__ wbt, int ld_t) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (size_t)rows * ld) return;
+    const int r = (int)(t / ld), c = (int)(t % ld);
+    const bf16_t v = (bf16_t)w[t];
+    wb[t] = v;
+    wbt[(size_t)c * ld_t + r] = v;
+}
+
 inline unsigned blocks_for(int64_t items, int per_block) { return (unsigned)((items + per_block - 1) / per_block); }
 
 }  // namespace
 
-int pad_rows_f32(const float *src, int64_t rows, int width, float *dst, int ld, const float *rowscale,
-                 hipStream_t st) {
+int pad_rows(const float *src, int64_t rows, int width, void *dst, int dst_dtype, int ld, const float *rowscale,
+             hipStream_t st) {
     if (rows <= 0) return GCN_OK;
-    k_pad_rows<<<dim3(blocks_for(rows * ld, kThreads)), dim3(kThreads), 0, st>>>(src, rows, width, dst, ld, rowscale);
+    const dim3 grid(blocks_for(rows * ld, kThreads));
+    if (dst_dtype == GCN_BF16)
+        k_pad_rows<bf16_t><<<grid, dim3(kThreads), 0, st>>>(src, rows, width, (bf16_t *)dst, ld, rowscale);
+    else
+        k_pad_rows<float><<<grid, dim3(kThreads), 0, st>>>(src, rows, width, (float *)dst, ld, rowscale);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }
 
-int unpad_rows_f32(const float *src, int ld, int64_t rows, int width, float *dst, const float *rowdiv,
-                   hipStream_t st) {
+int unpad_rows(const void *src, int src_dtype, int ld, int64_t rows, int width, float *dst, const float *rowdiv,
+               hipStream_t st) {
     if (rows <= 0) return GCN_OK;
-    k_unpad_rows<<<dim3(blocks_for(rows * width, kThreads)), dim3(kThreads), 0, st>>>(src, ld, rows, width, dst,
-                                                                                      rowdiv);
+    const dim3 grid(blocks_for(rows * width, kThreads));
+    if (src_dtype == GCN_BF16)
+        k_unpad_rows<bf16_t><<<grid, dim3(kThreads), 0, st>>>((const bf16_t *)src, ld, rows, width, dst, rowdiv);
+    else
+        k_unpad_rows<float><<<grid, dim3(kThreads), 0, st>>>((const float *)src, ld, rows, width, dst, rowdiv);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int weight_copies(const float *w, int rows, int ld, void *wb, void *wbt, int ld_t, hipStream_t st) {
+    k_weight_copies<<<dim3(blocks_for((int64_t)rows * ld, kThreads)), dim3(kThreads), 0, st>>>(
+        w, rows, ld, (bf16_t *)wb, (bf16_t *)wbt, ld_t);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }
@@ -190,13 +219,18 @@ int fill_zero(void *p, size_t bytes, hipStream_t st) {
 }
 
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
-                 const float *dinv, int64_t n_train, float *dzs, int ld_dz, double *loss_part, long long *corr_part,
-                 float *result, long long *result_correct, hipStream_t st) {
+                 const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
+                 long long *corr_part, float *result, long long *result_correct, hipStream_t st) {
     int blocks = (int)((n + 3) / 4);
     if (blocks > kLossBlocks) blocks = kLossBlocks;
     if (blocks < 1) blocks = 1;
-    k_loss<<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv,
-                                                    (float)(1.0 / (double)n_train), dzs, ld_dz, loss_part, corr_part);
+    const float inv = (float)(1.0 / (double)n_train);
+    if (dz_dtype == GCN_BF16)
+        k_loss<bf16_t><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
+                                                                (bf16_t *)dzs, ld_dz, loss_part, corr_part);
+    else
+        k_loss<float><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
+                                                               (float *)dzs, ld_dz, loss_part, corr_part);
     GCN_LAUNCH_CHECK();
     k_loss_final<<<dim3(1), dim3(kThreads), 0, st>>>(blocks, loss_part, corr_part, 1.0 / (double)n_train, result,
                                                      result_correct);

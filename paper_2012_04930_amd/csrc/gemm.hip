@@ -319,7 +319,11 @@ int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
         k_gemm<kTN, 4, 1, 1><<<dim3(mtiles, splits), dim3(kThreads), 0, st>>>(g);
     }
     GCN_LAUNCH_CHECK();
-    const size_t count4 = (size_t)M * (size_t)ldc / 4;   // ldc is a multiple of 16
+    return reduce_partials(partials, splits, (size_t)M * (size_t)ldc, c, st);
+}
+
+int reduce_partials(const float *partials, int splits, size_t count, float *c, hipStream_t st) {
+    const size_t count4 = count / 4;   // leading dimensions are multiples of 16
     k_reduce_partials<<<dim3((unsigned)((count4 + 63) / 64)), dim3(64), 0, st>>>(
         reinterpret_cast<const float4 *>(partials), splits, count4, reinterpret_cast<float4 *>(c));
     GCN_LAUNCH_CHECK();

@@ -6,8 +6,9 @@
 // times d_i^-1/2.  No value array is read: 4 bytes of column index per nonzero.  Entries past the
 // end of a row are replaced by column n, an all-zero input row, so inner loops need no lane masks.
 //
-// A group of LPR lanes covers one input row with one 16-byte load per lane (LPR * 4 >= leading
-// dimension), so every load instruction moves whole rows, contiguous in memory.
+// A group of LPR lanes covers one input row with one 16-byte load per lane (4 float32 or 8 bfloat16
+// elements; LPR * that >= leading dimension), so every load instruction moves whole rows, contiguous
+// in memory.  Sums are float32 whatever the storage type.
 //   heavy rows (degree >= kHeavyDegree): one wave per output row; its 64 / LPR lane groups take
 //     interleaved neighbours, column indices are wave-uniform and travel through the scalar path;
 //     the groups' partial sums meet in a cross-lane reduction at the end.
@@ -16,6 +17,7 @@
 // Workgroup ids are dealt round-robin over the XCDs, so block ids are remapped to give each XCD one
 // contiguous range of rows: neighbouring rows share neighbours, and each XCD has its own L2.
 #include "common.hpp"
+#include "dtypes.hpp"
 
 namespace gcn {
 
@@ -50,35 +52,35 @@ __device__ inline float finish(float v, const Epi &ep, int64_t row, int c) {
     return v;
 }
 
-__device__ inline void store_row_piece(float *__restrict__ out, int ld_out, int r, int sub, float4 a, float d,
+// The lane's piece of output row r (columns sub * V ...), scaled by d = d_r^-1/2 and finished.
+template <typename TOut, int V>
+__device__ inline void store_row_piece(TOut *__restrict__ out, int ld_out, int r, int sub, const float (&a)[V], float d,
                                        const Epi &ep) {
-    const int c0 = sub * 4;
-    float4 o;
-    o.x = finish(a.x * d, ep, r, c0 + 0);
-    o.y = finish(a.y * d, ep, r, c0 + 1);
-    o.z = finish(a.z * d, ep, r, c0 + 2);
-    o.w = finish(a.w * d, ep, r, c0 + 3);
-    reinterpret_cast<float4 *>(out + (int64_t)r * ld_out)[sub] = o;
+    const int c0 = sub * V;
+    float o[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) o[i] = finish(a[i] * d, ep, r, c0 + i);
+    store_elems<V>(out + (int64_t)r * ld_out + c0, o);
 }
 
 // One 16-byte piece of input row c: byte offset c * row_bytes + lane_bytes from t.  With NARROW the
 // whole input is below 4 GiB and the offset is formed in 32 bits (scalar base + 32-bit lane offset).
-template <bool NARROW>
-__device__ inline float4 load_piece(const float *__restrict__ t, int c, uint32_t row_bytes, uint32_t lane_bytes) {
+template <bool NARROW, typename TIn, int V>
+__device__ inline void load_piece(const TIn *__restrict__ t, int c, uint32_t row_bytes, uint32_t lane_bytes,
+                                  float (&v)[V]) {
     if (NARROW) {
         const uint32_t off = (uint32_t)c * row_bytes + lane_bytes;
-        return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(t) + off);
+        unpack16(reinterpret_cast<const TIn *>(reinterpret_cast<const char *>(t) + off), v);
     } else {
         const uint64_t off = (uint64_t)(uint32_t)c * row_bytes + lane_bytes;
-        return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(t) + off);
+        unpack16(reinterpret_cast<const TIn *>(reinterpret_cast<const char *>(t) + off), v);
     }
 }
 
-__device__ inline void add4(float4 &a, const float4 &v) {
-    a.x += v.x;
-    a.y += v.y;
-    a.z += v.z;
-    a.w += v.w;
+template <int V>
+__device__ inline void addv(float (&a)[V], const float (&v)[V]) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) a[i] += v[i];
 }
 
 // block id -> position in the row range, so that XCD x (block ids congruent x mod 8) walks one
@@ -89,13 +91,14 @@ __device__ inline int xcd_contiguous_block(int nblocks) {
 }
 
 // ------------------------------------------------------------------------------------------------ heavy rows
-template <int LPR, int U, bool NARROW>
+template <typename TIn, typename TOut, int LPR, int U, bool NARROW>
 __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ col,
                                                         const int32_t *__restrict__ perm,
                                                         const float *__restrict__ dinv, int zero_row,
-                                                        int64_t n_rows, const float *__restrict__ t, int ld_t,
-                                                        float *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+                                                        int64_t n_rows, const TIn *__restrict__ t, int ld_t,
+                                                        TOut *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+    constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
     constexpr int STEP = GPW * U;      // neighbours per unrolled step
     static_assert(STEP <= kColSlack, "the index prefetch may run one step past the end of col");
@@ -110,8 +113,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
     const int r = perm[s];
     const int64_t beg = rowptr[r], end = rowptr[r + 1];
     // lanes beyond the row's width re-read its first piece (in bounds, same cache line) and store nothing
-    const uint32_t lane_bytes = (sub * 4 < ld_t) ? sub * 16u : 0u;
-    const uint32_t row_bytes = (uint32_t)ld_t * 4u;
+    const uint32_t lane_bytes = (sub * V < ld_t) ? sub * 16u : 0u;
+    const uint32_t row_bytes = (uint32_t)ld_t * (uint32_t)sizeof(TIn);
 
     // group g takes entries e + u * GPW + g, u = 0..U-1; all addresses are wave-uniform
     auto fetch_indices = [&](int (&c)[U], int64_t e) {
@@ -128,60 +131,61 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
         }
     };
 
-    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float acc0[V], acc1[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc0[i] = acc1[i] = 0.0f;
     const int64_t full_end = beg + (end - beg) / STEP * STEP;
     int c[U];
     fetch_indices(c, beg);            // may read up to STEP entries past `end`: inside col + slack
     for (int64_t e = beg; e < full_end; e += STEP) {
         int cn[U];
         fetch_indices(cn, e + STEP);
-        float4 v[U];
+        float v[U][V];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = load_piece<NARROW>(t, c[u], row_bytes, lane_bytes);
+        for (int u = 0; u < U; ++u) load_piece<NARROW>(t, c[u], row_bytes, lane_bytes, v[u]);
 #pragma unroll
         for (int u = 0; u < U; u += 2) {
-            add4(acc0, v[u]);
-            add4(acc1, v[u + 1]);
+            addv(acc0, v[u]);
+            addv(acc1, v[u + 1]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) c[u] = cn[u];
     }
     if (full_end < end) {
         // last partial step: entries at or past `end` become the all-zero row
-        float4 v[U];
+        float v[U][V];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t pos = full_end + u * GPW + grp;
             const int cc = pos < end ? c[u] : zero_row;
-            v[u] = load_piece<NARROW>(t, cc, row_bytes, lane_bytes);
+            load_piece<NARROW>(t, cc, row_bytes, lane_bytes, v[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; u += 2) {
-            add4(acc0, v[u]);
-            add4(acc1, v[u + 1]);
+            addv(acc0, v[u]);
+            addv(acc1, v[u + 1]);
         }
     }
-    float4 a4 = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
+    float a[V];
 #pragma unroll
-    for (int d = LPR; d < 64; d <<= 1) {
-        a4.x += __shfl_xor(a4.x, d, 64);
-        a4.y += __shfl_xor(a4.y, d, 64);
-        a4.z += __shfl_xor(a4.z, d, 64);
-        a4.w += __shfl_xor(a4.w, d, 64);
+    for (int i = 0; i < V; ++i) {
+        a[i] = acc0[i] + acc1[i];
+#pragma unroll
+        for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
     }
-    if (grp == 0 && sub * 4 < ld_out) store_row_piece(out, ld_out, r, sub, a4, dinv[r], ep);
+    if (grp == 0 && sub * V < ld_out) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
 }
 
 // ------------------------------------------------------------------------------------------------ light rows
-template <int LPR, int U, bool NARROW>
+template <typename TIn, typename TOut, int LPR, int U, bool NARROW>
 __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restrict__ rowptr,
                                                          const int32_t *__restrict__ col,
                                                          const int32_t *__restrict__ perm,
                                                          const float *__restrict__ dinv, int zero_row,
-                                                         int64_t n_rows, const float *__restrict__ t, int ld_t,
-                                                         float *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+                                                         int64_t n_rows, const TIn *__restrict__ t, int ld_t,
+                                                         TOut *__restrict__ out, int ld_out, int nblocks, Epi ep) {
     static_assert(LPR % U == 0, "one index fetch feeds a whole number of unrolled steps");
+    constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;                 // rows per wave
     constexpr int RPB = (kThreads / 64) * GPW;    // rows per workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -190,8 +194,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
     if (blk >= nblocks) return;
     const int64_t s = (int64_t)blk * RPB + wave * GPW + grp;
     const bool live = s < n_rows;
-    const uint32_t lane_bytes = (sub * 4 < ld_t) ? sub * 16u : 0u;
-    const uint32_t row_bytes = (uint32_t)ld_t * 4u;
+    const uint32_t lane_bytes = (sub * V < ld_t) ? sub * 16u : 0u;
+    const uint32_t row_bytes = (uint32_t)ld_t * (uint32_t)sizeof(TIn);
     int64_t beg = 0, end = 0;
     int r = 0;
     if (live) {
@@ -199,8 +203,9 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
         beg = rowptr[r];
         end = rowptr[r + 1];
     }
-    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float acc0[V], acc1[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc0[i] = acc1[i] = 0.0f;
     int nxt = (beg + sub < end) ? col[beg + sub] : zero_row;
     for (int64_t e = beg; e < end; e += LPR) {
         const int mine = nxt;         // entry e + sub, or the zero row past the end
@@ -209,46 +214,48 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
         nxt = (e2 < end) ? col[e2] : zero_row;
         for (int k = 0; k < cnt; k += U) {
             int c[U];
-            float4 v[U];
+            float v[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) c[u] = __shfl(mine, grp * LPR + k + u, 64);
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = load_piece<NARROW>(t, c[u], row_bytes, lane_bytes);
-            if (U == 1) {
-                add4(acc0, v[0]);
-            } else {
+            for (int u = 0; u < U; ++u) load_piece<NARROW>(t, c[u], row_bytes, lane_bytes, v[u]);
 #pragma unroll
-                for (int u = 0; u + 1 < U; u += 2) {
-                    add4(acc0, v[u]);
-                    add4(acc1, v[u + 1]);
-                }
+            for (int u = 0; u + 1 < U; u += 2) {
+                addv(acc0, v[u]);
+                addv(acc1, v[u + 1]);
             }
         }
     }
-    if (live && sub * 4 < ld_out) {
-        float4 a4 = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
-        store_row_piece(out, ld_out, r, sub, a4, dinv[r], ep);
+    if (live && sub * V < ld_out) {
+        float a[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) a[i] = acc0[i] + acc1[i];
+        store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
     }
 }
 
 // true when every byte of the input (n + 1 rows) is addressable with a 32-bit offset
-inline bool narrow_ok(const SpmmArgs &a) { return (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * 4ull <= 0xffffffffull; }
+inline bool narrow_ok(const SpmmArgs &a, size_t elem) {
+    return (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * elem <= 0xffffffffull;
+}
 
-template <int LPR, int UW, int UG>
+template <typename TIn, typename TOut, int LPR, int UW, int UG>
 int launch(const SpmmArgs &a, hipStream_t st) {
     Epi ep{a.epilogue, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
-    const bool narrow = narrow_ok(a);
+    const bool narrow = narrow_ok(a, sizeof(TIn));
     const int zero_row = (int)a.n;
+    const TIn *t = static_cast<const TIn *>(a.t);
+    TOut *out = static_cast<TOut *>(a.out);
     if (a.n_heavy > 0) {
         constexpr int RPB = kThreads / 64;
         const int nblocks = (int)((a.n_heavy + RPB - 1) / RPB);
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
-            k_spmm_wave<LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, a.t, a.ld_t, a.out, a.ld_out, nblocks, ep);
+            k_spmm_wave<TIn, TOut, LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, nblocks, ep);
         else
-            k_spmm_wave<LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, a.t, a.ld_t, a.out, a.ld_out, nblocks, ep);
+            k_spmm_wave<TIn, TOut, LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, nblocks, ep);
         GCN_LAUNCH_CHECK();
     }
     const int64_t n_light = a.n - a.n_heavy;
@@ -257,36 +264,42 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int nblocks = (int)((n_light + RPB - 1) / RPB);
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
-            k_spmm_group<LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, a.t, a.ld_t, a.out, a.ld_out, nblocks,
-                ep);
+            k_spmm_group<TIn, TOut, LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, nblocks, ep);
         else
-            k_spmm_group<LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, a.t, a.ld_t, a.out, a.ld_out, nblocks,
-                ep);
+            k_spmm_group<TIn, TOut, LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, nblocks, ep);
         GCN_LAUNCH_CHECK();
     }
     return GCN_OK;
+}
+
+template <typename TIn, typename TOut>
+int launch_by_width(const SpmmArgs &a, hipStream_t st) {
+    const int pieces = (a.ld_t + Piece<TIn>::kElems - 1) / Piece<TIn>::kElems;   // 16-byte pieces per row
+    if (pieces <= 4) return launch<TIn, TOut, 4, 2, 4>(a, st);
+    if (pieces <= 8) return launch<TIn, TOut, 8, 2, 8>(a, st);
+    if (pieces <= 16) return launch<TIn, TOut, 16, 4, 8>(a, st);
+    if (pieces <= 32) return launch<TIn, TOut, 32, 8, 8>(a, st);
+    return launch<TIn, TOut, 64, 8, 8>(a, st);
 }
 
 }  // namespace
 
 int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     if (a.n <= 0) return GCN_OK;
-    if (a.ld_t % 4 != 0 || a.ld_out % 4 != 0 || a.ld_out > a.ld_t || a.ld_t > 256 || a.n_heavy < 0 ||
-        a.n_heavy > a.n) {
-        set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld)", a.ld_t, a.ld_out,
-                  (long long)a.n_heavy, (long long)a.n);
+    const int v_in = a.t_dtype == GCN_BF16 ? 8 : 4;
+    if (a.ld_t % 8 != 0 || a.ld_out % 8 != 0 || a.ld_out > a.ld_t || a.ld_t > 64 * v_in || a.n_heavy < 0 ||
+        a.n_heavy > a.n || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
+        set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld, types %d -> %d)", a.ld_t, a.ld_out,
+                  (long long)a.n_heavy, (long long)a.n, a.t_dtype, a.out_dtype);
         return GCN_EINVAL;
     }
     timing_begin(a.width, st);
     int rc;
-    const int vecs = a.ld_t / 4;
-    if (vecs <= 4) rc = launch<4, 2, 4>(a, st);
-    else if (vecs <= 8) rc = launch<8, 2, 8>(a, st);
-    else if (vecs <= 16) rc = launch<16, 4, 8>(a, st);
-    else if (vecs <= 32) rc = launch<32, 8, 8>(a, st);
-    else rc = launch<64, 8, 8>(a, st);
+    if (a.t_dtype == GCN_F32) rc = launch_by_width<float, float>(a, st);
+    else if (a.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(a, st);
+    else rc = launch_by_width<bf16_t, bf16_t>(a, st);
     timing_end(st);
     return rc;
 }

@@ -240,3 +240,40 @@ def test_config_c4_full_reddit_shape(B, oracle):
     _, gpu = H.gpu_epoch(B, g, wl)
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
     H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+# ------------------------------------------------------------------ bfloat16 storage, fp32 accumulation (tolerance 2e-2)
+@pytest.mark.parametrize("width", [7, 47, 100, 256, 300])
+def test_aggregate_bf16_storage(B, oracle, width):
+    wl = workloads.chung_lu_mid(scale=0.03)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(width, 2, wl.n * width).reshape(wl.n, width)
+    got = B.gcn_aggregate(g, torch.from_numpy(x).cuda(), dtype=B.GCN_BF16).cpu().numpy()
+    H.assert_close(got, oracle.aggregate(og, x), rtol=H.RTOL_BF16, what="bf16 A_hat x, width %d" % width)
+    # with an input that is exactly representable the only error left is fp32 summation order
+    xi = np.round(x * 4).astype(np.float32) / 4 * (og.deg[:, None] == og.deg[:, None])
+    ones = np.ones((wl.n, 8), dtype=np.float32)
+    got1 = B.gcn_aggregate(g, torch.from_numpy(ones).cuda(), dtype=B.GCN_BF16).cpu().numpy()
+    H.assert_close(got1, oracle.aggregate(og, ones), rtol=H.RTOL_BF16, what="bf16 A_hat 1")
+
+
+@pytest.mark.parametrize("make", [lambda: workloads.tiny(),
+                                  lambda: workloads.chung_lu_mid(scale=0.1),
+                                  lambda: workloads.reddit_partition(scale=0.08),
+                                  lambda: workloads.rmat_large(scale=0.004)],
+                         ids=["tiny", "chung_lu_10k", "partition_3.7k", "rmat_9.6k_3layers"])
+def test_full_step_bf16_storage(B, oracle, make):
+    wl = make()
+    g = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
+    _, gpu = H.gpu_epoch(B, g, wl, dtype=B.GCN_BF16)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True)
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
+
+
+def test_model_and_graph_storage_types_must_agree(B):
+    wl = workloads.tiny(n=256)
+    g = H.gpu_graph(B, wl)
+    with pytest.raises(B.GcnError) as e:
+        B.gcn_model_create(g, wl.dims, dtype=B.GCN_BF16)
+    assert e.value.code == -1
