@@ -75,17 +75,15 @@ def main() -> int:
     t0 = time.perf_counter()
     wl = workloads.BY_NAME[args.workload](seed=args.seed)
     t_gen = time.perf_counter() - t0
-    if wl.dtype != "f32":
-        print("bench.py: workload %s needs bf16 storage, which this build does not have yet" % args.workload,
-              file=sys.stderr)
-        return 2
+    dtype = B.GCN_BF16 if wl.dtype == "bf16" else B.GCN_F32
+    esize = 2 if dtype == B.GCN_BF16 else 4
 
     t0 = time.perf_counter()
-    g = H.gpu_graph(B, wl)
+    g = H.gpu_graph(B, wl, dtype=dtype)
     torch.cuda.synchronize()
     t_create = time.perf_counter() - t0
     info = B.gcn_graph_info(g)
-    m = B.gcn_model_create(g, wl.dims)
+    m = B.gcn_model_create(g, wl.dims, dtype=dtype)
     B.gcn_set_weights(m, wl.weights)
 
     def epoch():
@@ -129,18 +127,18 @@ def main() -> int:
         cnt, ms = B.gcn_timing_read(w)
         if cnt:
             avg = ms / cnt
-            by = gather_bytes(E, n, w)
+            by = gather_bytes(E, n, w, esize)
             spmm["w%d" % w] = {"launches": cnt, "avg_ms": round(avg, 5), "gather_GBps": round(by / avg / 1e6, 1),
                                "alu_frac_fp32": round(2.0 * E * w / (avg * 1e-3) / (FP32_PEAK_TFLOPS * 1e12), 4)}
     dom_w = wl.dims[1]
     roofline = None
     if "w%d" % dom_w in spmm:
         avg = spmm["w%d" % dom_w]["avg_ms"]
-        achieved = gather_bytes(E, n, dom_w) / avg / 1e6
+        achieved = gather_bytes(E, n, dom_w, esize) / avg / 1e6
         roofline = {"bound": "hbm", "kernel": "aggregation (k_spmm_wave + k_spmm_group), width %d" % dom_w,
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name, dom_w),
-                    "bytes_per_launch": gather_bytes(E, n, dom_w), "avg_launch_ms": avg}
+                    "bytes_per_launch": gather_bytes(E, n, dom_w, esize), "avg_launch_ms": avg}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -149,6 +147,7 @@ def main() -> int:
         og = O.canonicalise(wl.n, wl.rowptr, wl.col)
         ws = [w.astype(np.float64) for w in wl.weights]
         x64 = wl.x.astype(np.float64)
+        del wl.x
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         n_ep, dt = 0, 0.0
         t0 = time.perf_counter()
@@ -165,7 +164,7 @@ def main() -> int:
         "metric": "GCN train epochs/sec (fwd+bwd) on one partition; SpMM HBM GB/s vs peak",
         "value": round(args.steps / secs, 3), "unit": "epochs/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(1e3 * secs / args.steps, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "n_local": wl.n_local, "nnz_A_plus_I": E, "dims": wl.dims,
                    "lr": wl.lr, "optimizer": "sgd", "seed": args.seed},
         "roofline": roofline, "cpu_baseline": cpu,

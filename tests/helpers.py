@@ -84,7 +84,7 @@ def gate_check(gpu_h, tr, rtol=RTOL_F32):
             assert np.abs(z[differ]).max() <= rtol * rms, "gate of layer %d differs away from zero" % (l + 1)
 
 
-def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True, gpu=None, bf16=False):
+def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True, gpu=None, bf16=False, say=None):
     """One oracle epoch.  With gpu given, the backward pass takes the ReLU decisions from the GPU's
     activations (checked by gate_check to differ from the oracle's own only at pre-activations ~ 0).
     With bf16, the oracle computes in fp64 on X and W rounded to bfloat16 (what the GPU path stores);
@@ -93,7 +93,11 @@ def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True, gpu=None,
     master = [w.astype(np.float64) for w in wl.weights]
     x = bf16_round(wl.x) if bf16 else wl.x
     ws = [bf16_round(w).astype(np.float64) for w in wl.weights] if bf16 else master
+    if say:
+        say("forward")
     tr = O.forward(og, x, ws, p=dropout_p, training=training, seed=seed, epoch=0)
+    if say:
+        say("backward")
     gate = None
     if gpu is not None:
         gate_check(gpu["H"], tr, RTOL_BF16 if bf16 else RTOL_F32)

@@ -1,4 +1,6 @@
 """GPU library vs CPU oracle, element by element, on the same seeded inputs (run with -m gpu)."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -227,9 +229,17 @@ def test_config_c2_full_size(B, oracle):
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
+def _say(capsys, text):
+    """Progress line that reaches the terminal even under output capture (long tests must not look hung)."""
+    with capsys.disabled():
+        print("\n    [%s] %s" % (time.strftime("%H:%M:%S"), text), end="", flush=True)
+
+
 @pytest.mark.timeout(900)
-def test_config_c4_full_reddit_shape(B, oracle):
+def test_config_c4_full_reddit_shape(B, oracle, capsys):
+    _say(capsys, "c4: generating 232,965 vertices")
     wl = workloads.reddit_full()                       # 232,965 vertices, ~114 M nonzeros, rows up to ~10 k entries
+    _say(capsys, "c4: graph preparation on GPU and in the oracle")
     g = H.gpu_graph(B, wl)
     og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
     rowptr, col, deg, _ = [t.cpu().numpy() for t in B.gcn_graph_get_csr(g)]
@@ -237,8 +247,11 @@ def test_config_c4_full_reddit_shape(B, oracle):
     np.testing.assert_array_equal(col, og.col)
     np.testing.assert_array_equal(deg, og.deg)
     del rowptr, col, deg
+    _say(capsys, "c4: GPU epoch")
     _, gpu = H.gpu_epoch(B, g, wl)
+    _say(capsys, "c4: oracle epoch")
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    _say(capsys, "c4: comparing")
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
@@ -277,3 +290,23 @@ def test_model_and_graph_storage_types_must_agree(B):
     with pytest.raises(B.GcnError) as e:
         B.gcn_model_create(g, wl.dims, dtype=B.GCN_BF16)
     assert e.value.code == -1
+
+
+@pytest.mark.timeout(1700)
+def test_config_c5_full_size_bf16(B, oracle, capsys):
+    _say(capsys, "c5: generating 2.4 M vertices")
+    wl = workloads.rmat_large()                        # 2.4 M vertices, 122.4 M nonzeros, 100 -> 256 -> 256 -> 47
+    _say(capsys, "c5: graph preparation on GPU and in the oracle")
+    g = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    rowptr, col, deg, _ = [t.cpu().numpy() for t in B.gcn_graph_get_csr(g)]
+    np.testing.assert_array_equal(rowptr, og.rowptr)
+    np.testing.assert_array_equal(col, og.col)
+    np.testing.assert_array_equal(deg, og.deg)
+    del rowptr, col, deg, og
+    _say(capsys, "c5: GPU epoch")
+    _, gpu = H.gpu_epoch(B, g, wl, dtype=B.GCN_BF16)
+    _say(capsys, "c5: oracle epoch (about a minute of fp64 loops)")
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True, say=lambda t: _say(capsys, "c5: oracle " + t))
+    _say(capsys, "c5: comparing")
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
