@@ -117,6 +117,11 @@ struct gcn_model {
     float *result = nullptr;        // [0] loss [1] accuracy
     long long *result_correct = nullptr;
     bool have_forward = false, have_loss = false, have_backward = false, trained_forward = false;
+    // Layer 1 in aggregate-first form: P = A_hat X is computed once (X never changes), then
+    // Z_1 = P W_1 and dW_1 = P^T dZ_1 need no aggregation at all.
+    bool l1_cached = false;
+    void *pax = nullptr;  // (n + 1) x ldf, storage type
+    void *xs = nullptr;   // (n + 1) x ldf: D^-1/2 X, only used while P is built
 };
 
 namespace {
@@ -168,12 +173,25 @@ void carve_model(Carver &c, gcn_model &m) {
                                           : gemm_tn_partial_floats(n, ly.ld_in, ly.ld_out);
         if (need > pf) pf = need;
     }
+    if (m.l1_cached) {
+        const size_t es = m.dtype == GCN_BF16 ? 2 : 4;
+        m.pax = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
+        m.xs = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
+    }
     m.partial_floats = pf;
     m.partials = c.take<float>(pf);
     m.loss_part = c.take<double>(kLossBlocks);
     m.corr_part = c.take<long long>(kLossBlocks);
     m.result = c.take<float>(4);
     m.result_correct = c.take<long long>(2);
+}
+
+// "cache_ax" knob: 0 = never, 1 = when the input is not wider than the first hidden layer (default), 2 = always.
+// Needs at least two layers (the one-layer model's output are float logits straight from the aggregation).
+bool want_l1_cached(int32_t n_layers, const int32_t *dims) {
+    const int64_t knob = tunable("cache_ax", 1);
+    if (n_layers < 2 || knob <= 0) return false;
+    return knob >= 2 || dims[0] <= dims[1];
 }
 
 int check_dims(int32_t n_layers, const int32_t *dims) {
@@ -371,7 +389,7 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     if (rc) return rc;
     rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
     if (rc) return rc;
-    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, dtype, ld, z, GCN_F32, ld, width,
+    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, dtype, ld, z, GCN_F32, ld, ld, width,
                kEpiNone, 0u, 1.0f, 0ull};
     rc = spmm_launch(a, st);
     if (rc) return rc;
@@ -388,6 +406,7 @@ int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_
     m.g = g;
     m.dtype = dtype;
     m.L = n_layers;
+    m.l1_cached = want_l1_cached(n_layers, dims);
     for (int l = 0; l < n_layers; ++l)
         m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
@@ -433,13 +452,27 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     m->dtype = dtype;
     m->p = dropout_p;
     m->seed = seed;
+    m->l1_cached = want_l1_cached(n_layers, dims);
     for (int l = 0; l < n_layers; ++l)
         m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(workspace);
     carve_model(c, *m);
     // zero everything once: padding columns, the extra zero rows and the weights start at zero
-    rc = fill_zero(workspace, need, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    rc = fill_zero(workspace, need, st);
+    if (!rc && m->l1_cached) {
+        // P = A_hat X, in column slabs the aggregation kernel can cover with one wave per row
+        rc = scale_rows(g->x, m->xs, dtype, g->n, g->ldf, g->pb.dinv, st);
+        const int slab = dtype == GCN_BF16 ? 512 : 256;
+        const size_t es = dtype == GCN_BF16 ? 2 : 4;
+        for (int c0 = 0; !rc && c0 < g->ldf; c0 += slab) {
+            const int cols = g->ldf - c0 < slab ? g->ldf - c0 : slab;
+            SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, (const char *)m->xs + c0 * es,
+                       dtype, g->ldf, (char *)m->pax + c0 * es, dtype, g->ldf, cols, g->f, kEpiNone, 0u, 1.0f, 0ull};
+            rc = spmm_launch(a, st);
+        }
+    }
     if (rc) {
         delete m;
         return rc;
@@ -509,8 +542,12 @@ int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_fl
         case GCN_T_DW: src = ly.dw; src_dtype = GCN_F32; rows = ly.d_in; ok = m->have_backward; break;
         case GCN_T_H: src = ly.h; ok = m->have_forward && layer < m->L; break;
         case GCN_T_LOGITS: src = ly.h; src_dtype = GCN_F32; ok = m->have_forward; break;
-        case GCN_T_G: src = ly.g; ok = m->have_backward; break;
-        case GCN_T_DZ: src = ly.dzs; rowdiv = m->g->pb.dinv; ok = m->have_backward; break;
+        case GCN_T_G: src = ly.g; ok = m->have_backward && !(layer == 1 && m->l1_cached); break;
+        case GCN_T_DZ:
+            src = ly.dzs;
+            rowdiv = (layer == 1 && m->l1_cached) ? nullptr : m->g->pb.dinv;   // stored without D^-1/2 in that case
+            ok = m->have_backward;
+            break;
         default: ok = false;
     }
     if (!ok || !src) {
@@ -536,21 +573,34 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
     int ld_prev = g->ldf;
     for (int l = 1; l <= m->L; ++l) {
         Layer &ly = m->layers[l - 1];
+        Activation act{l < m->L ? kActRelu : kActNone, ly.d_out, 0u, 1.0f, 0ull};
+        if (l < m->L && training && m->p > 0.0f) {
+            act.drop_threshold = (uint32_t)std::floor((double)m->p * 4294967296.0);
+            act.keep_scale = (float)(1.0 / (1.0 - (double)m->p));
+            act.drop_key = host_mix64(host_mix64(m->seed) ^ (m->epoch * 0xD1B54A32D192ED03ull) ^
+                                      ((uint64_t)l * 0x8CB92BA72F3D8DD7ull));
+        }
+        if (l == 1 && m->l1_cached) {
+            // H_1 = act(P W_1), P = A_hat X
+            int rc = bf ? gemm_bf16_nn(m->pax, g->ldf, ly.wbt, ly.ld_in, ly.h, ly.ld_out, g->n, ly.ld_in, ly.ld_out, nullptr,
+                                       &act, st)
+                        : gemm_nn((const float *)m->pax, g->ldf, ly.w, ly.ld_out, (float *)ly.h, ly.ld_out, g->n, ly.ld_in,
+                                  ly.ld_out, nullptr, &act, st);
+            if (rc) return rc;
+            h_prev = ly.h;
+            ld_prev = ly.ld_out;
+            continue;
+        }
         // T = D^-1/2 (H_{l-1} W_l)
         int rc = bf ? gemm_bf16_nn(h_prev, ld_prev, ly.wbt, ly.ld_in, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
-                                   g->pb.dinv, st)
+                                   g->pb.dinv, nullptr, st)
                     : gemm_nn((const float *)h_prev, ld_prev, ly.w, ly.ld_out, (float *)ly.t, ly.ld_out, g->n, ly.ld_in,
-                              ly.ld_out, g->pb.dinv, st);
+                              ly.ld_out, g->pb.dinv, nullptr, st);
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
         SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.t, m->dtype, ly.ld_out, ly.h,
-                   l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.d_out, l < m->L ? kEpiRelu : kEpiNone, 0u, 1.0f, 0ull};
-        if (l < m->L && training && m->p > 0.0f) {
-            a.drop_threshold = (uint32_t)std::floor((double)m->p * 4294967296.0);
-            a.keep_scale = (float)(1.0 / (1.0 - (double)m->p));
-            a.drop_key = host_mix64(host_mix64(m->seed) ^ (m->epoch * 0xD1B54A32D192ED03ull) ^
-                                    ((uint64_t)l * 0x8CB92BA72F3D8DD7ull));
-        }
+                   l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out, ly.d_out, l < m->L ? kEpiRelu : kEpiNone,
+                   act.drop_threshold, act.keep_scale, act.drop_key};
         rc = spmm_launch(a, st);
         if (rc) return rc;
         h_prev = ly.h;
@@ -609,9 +659,25 @@ int gcn_backward(gcn_model *m, void *stream) {
     const bool bf = m->dtype == GCN_BF16;
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
+        if (l == 1 && m->l1_cached) {
+            // dW_1 = P^T dZ_1  (dzs of layer 1 was written without D^-1/2)
+            int rc;
+            if (bf) {
+                int splits = 0;
+                rc = gemm_bf16_tn_partials(m->pax, g->ldf, ly.dzs, ly.ld_out, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
+                                           m->partials, m->partial_floats, &splits, st);
+                if (rc) return rc;
+                rc = reduce_partials(m->partials, splits, (size_t)ly.ld_in * ly.ld_out, ly.dw, st);
+            } else {
+                rc = gemm_tn((const float *)m->pax, g->ldf, (const float *)ly.dzs, ly.ld_out, ly.dw, ly.ld_out, g->n,
+                             ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
+            }
+            if (rc) return rc;
+            continue;
+        }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
         SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.dzs, m->dtype, ly.ld_out, ly.g,
-                   m->dtype, ly.ld_out, ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
+                   m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G
@@ -630,10 +696,11 @@ int gcn_backward(gcn_model *m, void *stream) {
         if (l > 1) {
             // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
             Layer &lp = m->layers[l - 2];
+            const float *next_scale = (l == 2 && m->l1_cached) ? nullptr : g->pb.dinv;   // no aggregation follows
             rc = bf ? gemm_bf16_nt(ly.g, ly.ld_out, ly.wb, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out,
-                                   g->pb.dinv, lp.h, lp.ld_out, keep_scale, st)
+                                   next_scale, lp.h, lp.ld_out, keep_scale, st)
                     : gemm_nt((const float *)ly.g, ly.ld_out, ly.w, ly.ld_out, (float *)lp.dzs, lp.ld_out, g->n,
-                              ly.ld_out, lp.ld_out, g->pb.dinv, (const float *)lp.h, lp.ld_out, keep_scale, st);
+                              ly.ld_out, lp.ld_out, next_scale, (const float *)lp.h, lp.ld_out, keep_scale, st);
             if (rc) return rc;
         }
     }

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/gcn355.h"
+#include "epilogue.hpp"
 
 namespace gcn {
 
@@ -96,6 +97,8 @@ int unpad_rows(const void *src, int src_dtype, int ld, int64_t rows, int width, 
 // bfloat16 copies of w [rows x ld]: same layout (wb) and transposed [ld x ld_t] (wbt)
 int weight_copies(const float *w, int rows, int ld, void *wb, void *wbt, int ld_t, hipStream_t st);
 int fill_zero(void *p, size_t bytes, hipStream_t st);
+// dst[r, :] = rowscale[r] * src[r, :] for matrices of the same storage type and leading dimension
+int scale_rows(const void *src, void *dst, int dtype, int64_t rows, int ld, const float *rowscale, hipStream_t st);
 
 // Loss / accuracy / dLoss/dlogits (scaled by dinv for the aggregation that follows).
 constexpr int kLossBlocks = 512;
@@ -125,7 +128,8 @@ struct SpmmArgs {
     void *out;          // float or bfloat16 (bfloat16 only from a bfloat16 input)
     int out_dtype;
     int ld_out;
-    int width;          // true width (<= ld)
+    int cols;           // columns handled by this launch (multiple of 8, <= both leading dimensions)
+    int width;          // true width of the whole matrix (element numbering of the dropout mask)
     int epilogue;
     // dropout (epilogue kEpiRelu, training): threshold 0 = keep everything
     uint32_t drop_threshold;
@@ -137,11 +141,11 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st);
 // ---------------------------------------------------------------------------------------------
 // Dense products on the matrix cores (gemm.hip).  All leading dimensions are multiples of 16 and the
 // padding columns/rows of the operands are zero.
-//   nn:  c[m, :] = rowscale[m] * (a[m, :] b)                a: M x K,  b: K x N,  c: M x N
+//   nn:  c[m, :] = act(rowscale[m] * (a[m, :] b))           a: M x K,  b: K x N,  c: M x N
 //   nt:  c[m, :] = rowscale[m] * scale * [gate[m, :] > 0] * (a[m, :] b^T)      b: N x K
 //   tn:  c = a^T b  reduced over the M rows of a and b in fixed order (split over row ranges)
 int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, hipStream_t st);
+            const float *rowscale, const Activation *act /* may be null */, hipStream_t st);
 int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
             const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st);
 size_t gemm_tn_partial_floats(int64_t rows, int M, int N);
@@ -153,7 +157,7 @@ int reduce_partials(const float *partials, int splits, size_t count, float *c, h
 // bfloat16 operands, float32 accumulation (gemm_bf16.hip).  a, b, c, gate are bfloat16 matrices; bt / b hold the
 // second operand with the shared dimension contiguous: nn takes W^T [N x K], nt takes W [N x K].
 int gemm_bf16_nn(const void *a, int lda, const void *bt, int ldb, void *c, int ldc, int64_t M, int K, int N,
-                 const float *rowscale, hipStream_t st);
+                 const float *rowscale, const Activation *act /* may be null */, hipStream_t st);
 int gemm_bf16_nt(const void *a, int lda, const void *b, int ldb, void *c, int ldc, int64_t M, int K, int N,
                  const float *rowscale, const void *gate, int ldg, float scale, hipStream_t st);
 size_t gemm_bf16_tn_partial_floats(int64_t rows, int M, int N);

@@ -38,6 +38,14 @@ __global__ void k_unpad_rows(const TSrc *__restrict__ src, int ld, int64_t rows,
     dst[t] = v;
 }
 
+template <typename T>
+__global__ void k_scale_rows(const T *__restrict__ src, T *__restrict__ dst, int64_t rows, int ld,
+                             const float *__restrict__ rowscale) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * ld) return;
+    dst[t] = narrow<T>(widen(src[t]) * rowscale[t / ld]);
+}
+
 __global__ void k_fill_zero(uint32_t *__restrict__ p, size_t words) {
     size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -193,6 +201,17 @@ int unpad_rows(const void *src, int src_dtype, int ld, int64_t rows, int width, 
         k_unpad_rows<bf16_t><<<grid, dim3(kThreads), 0, st>>>((const bf16_t *)src, ld, rows, width, dst, rowdiv);
     else
         k_unpad_rows<float><<<grid, dim3(kThreads), 0, st>>>((const float *)src, ld, rows, width, dst, rowdiv);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int scale_rows(const void *src, void *dst, int dtype, int64_t rows, int ld, const float *rowscale, hipStream_t st) {
+    if (rows <= 0) return GCN_OK;
+    const dim3 grid(blocks_for(rows * ld, kThreads));
+    if (dtype == GCN_BF16)
+        k_scale_rows<bf16_t><<<grid, dim3(kThreads), 0, st>>>((const bf16_t *)src, (bf16_t *)dst, rows, ld, rowscale);
+    else
+        k_scale_rows<float><<<grid, dim3(kThreads), 0, st>>>((const float *)src, (float *)dst, rows, ld, rowscale);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -12,6 +12,7 @@
 // Which two k of the 16 a lane pair feeds at each step is free (a sum is a sum): lane half h feeds
 // k = 8 h + s at step s, so the A fragment is two 16-byte LDS reads.
 #include "common.hpp"
+#include "epilogue.hpp"
 
 namespace gcn {
 
@@ -40,6 +41,7 @@ struct GemmArgs {
     int ldg;
     float scale;
     int64_t rows_per_split;  // tn
+    Activation act;          // nn: applied after the row scale
 };
 
 template <int MODE, int WM, int WN, int TN>
@@ -193,6 +195,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
                 float x = acc[t][v];
                 if (MODE == kNN) {
                     if (g.rowscale) x *= g.rowscale[row];
+                    x = activate(x, g.act, row, col);
                 } else if (MODE == kNT) {
                     const float gt = g.gate ? g.gate[row * g.ldg + col] : 1.0f;
                     x = gt > 0.0f ? x * g.scale : 0.0f;
@@ -268,13 +271,13 @@ bool check_ld(int lda, int ldb, int ldc) { return lda % 16 == 0 && ldb % 16 == 0
 }  // namespace
 
 int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, hipStream_t st) {
+            const float *rowscale, const Activation *act, hipStream_t st) {
     if (M <= 0) return GCN_OK;
     if (!check_ld(lda, ldb, ldc) || K % BK != 0 || K > lda || N > ldb) {
         set_error("gemm_nn: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0, act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     return launch_rows<kNN>(g, st);
 }
 
@@ -285,7 +288,7 @@ int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
         set_error("gemm_nt: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     return launch_rows<kNT>(g, st);
 }
 
@@ -308,7 +311,7 @@ int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
     }
     int64_t per = (rows + splits - 1) / splits;
     per = (per + BK - 1) / BK * BK;
-    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per};
+    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per, Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     const int mtiles = (M + 127) / 128;
     if (N > 64) {
         const int ntiles = (N + 127) / 128;

@@ -13,6 +13,7 @@
 // turns 4 x 8 blocks round in registers before the LDS store.
 #include "common.hpp"
 #include "dtypes.hpp"
+#include "epilogue.hpp"
 
 namespace gcn {
 
@@ -42,6 +43,7 @@ struct Args {
     int ldg;
     float scale;
     int64_t rows_per_split;
+    Activation act;   // nn: applied after the row scale
 };
 
 __device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
                         x = gt > 0.0f ? x * g.scale : 0.0f;
                     }
                     if (g.rowscale) x *= g.rowscale[row];
+                    if (MODE == kNN) x = activate(x, g.act, row, col);
                     static_cast<bf16_t *>(g.c)[row * g.ldc + col] = (bf16_t)x;
                 }
             }
@@ -243,13 +246,14 @@ bool ok_ld(int lda, int ldb, int ldc) { return lda % 16 == 0 && ldb % 16 == 0 &&
 }  // namespace
 
 int gemm_bf16_nn(const void *a, int lda, const void *bt, int ldb, void *c, int ldc, int64_t M, int K, int N,
-                 const float *rowscale, hipStream_t st) {
+                 const float *rowscale, const Activation *act, hipStream_t st) {
     if (M <= 0) return GCN_OK;
     if (!ok_ld(lda, ldb, ldc) || K % 16 != 0 || K > lda || K > ldb) {
         set_error("gemm_bf16_nn: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    Args g{(const bf16_t *)a, lda, (const bf16_t *)bt, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0};
+    Args g{(const bf16_t *)a, lda, (const bf16_t *)bt, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0,
+           act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     return launch_rows<kNN>(g, st);
 }
 
@@ -260,7 +264,8 @@ int gemm_bf16_nt(const void *a, int lda, const void *b, int ldb, void *c, int ld
         set_error("gemm_bf16_nt: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    Args g{(const bf16_t *)a, lda, (const bf16_t *)b, ldb, c, ldc, M, K, N, rowscale, (const bf16_t *)gate, ldg, scale, 0};
+    Args g{(const bf16_t *)a, lda, (const bf16_t *)b, ldb, c, ldc, M, K, N, rowscale, (const bf16_t *)gate, ldg, scale, 0,
+           Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     return launch_rows<kNT>(g, st);
 }
 
@@ -293,7 +298,8 @@ int gemm_bf16_tn_partials(const void *a, int lda, const void *b, int ldb, int ld
     }
     int64_t per = (rows + splits - 1) / splits;
     per = (per + BK - 1) / BK * BK;
-    Args g{(const bf16_t *)a, lda, (const bf16_t *)b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per};
+    Args g{(const bf16_t *)a, lda, (const bf16_t *)b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per,
+           Activation{kActNone, 0, 0u, 1.0f, 0ull}};
     const int mtiles = (M + 127) / 128;
     if (N > 64) {
         const int ntiles = (N + 127) / 128;

@@ -18,6 +18,7 @@
 // contiguous range of rows: neighbouring rows share neighbours, and each XCD has its own L2.
 #include "common.hpp"
 #include "dtypes.hpp"
+#include "epilogue.hpp"
 
 namespace gcn {
 
@@ -25,32 +26,9 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ inline uint64_t mix64(uint64_t z) {
-    z += 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
+typedef Activation Epi;
 
-struct Epi {
-    int kind;
-    int width;
-    uint32_t drop_threshold;
-    float keep_scale;
-    uint64_t drop_key;
-};
-
-__device__ inline float finish(float v, const Epi &ep, int64_t row, int c) {
-    if (ep.kind == kEpiRelu) {
-        v = v > 0.0f ? v : 0.0f;
-        if (ep.drop_threshold != 0u) {
-            uint64_t e = (uint64_t)row * (uint64_t)ep.width + (uint64_t)c;
-            uint64_t h = mix64(ep.drop_key + e * 0x9E3779B97F4A7C15ull);
-            v = ((uint32_t)(h >> 32) >= ep.drop_threshold) ? v * ep.keep_scale : 0.0f;
-        }
-    }
-    return v;
-}
+__device__ inline float finish(float v, const Epi &ep, int64_t row, int c) { return activate(v, ep, row, c); }
 
 // The lane's piece of output row r (columns sub * V ...), scaled by d = d_r^-1/2 and finished.
 template <typename TOut, int V>
@@ -97,7 +75,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
                                                         const int32_t *__restrict__ perm,
                                                         const float *__restrict__ dinv, int zero_row,
                                                         int64_t n_rows, const TIn *__restrict__ t, int ld_t,
-                                                        TOut *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+                                                        TOut *__restrict__ out, int ld_out, int cols, int nblocks,
+                                                        Epi ep) {
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
     constexpr int STEP = GPW * U;      // neighbours per unrolled step
@@ -113,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
     const int r = perm[s];
     const int64_t beg = rowptr[r], end = rowptr[r + 1];
     // lanes beyond the row's width re-read its first piece (in bounds, same cache line) and store nothing
-    const uint32_t lane_bytes = (sub * V < ld_t) ? sub * 16u : 0u;
+    const uint32_t lane_bytes = (sub * V < cols) ? sub * 16u : 0u;
     const uint32_t row_bytes = (uint32_t)ld_t * (uint32_t)sizeof(TIn);
 
     // group g takes entries e + u * GPW + g, u = 0..U-1; all addresses are wave-uniform
@@ -173,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
 #pragma unroll
         for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
     }
-    if (grp == 0 && sub * V < ld_out) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
+    if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
 }
 
 // ------------------------------------------------------------------------------------------------ light rows
@@ -183,7 +162,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
                                                          const int32_t *__restrict__ perm,
                                                          const float *__restrict__ dinv, int zero_row,
                                                          int64_t n_rows, const TIn *__restrict__ t, int ld_t,
-                                                         TOut *__restrict__ out, int ld_out, int nblocks, Epi ep) {
+                                                         TOut *__restrict__ out, int ld_out, int cols, int nblocks,
+                                                         Epi ep) {
     static_assert(LPR % U == 0, "one index fetch feeds a whole number of unrolled steps");
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;                 // rows per wave
@@ -194,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
     if (blk >= nblocks) return;
     const int64_t s = (int64_t)blk * RPB + wave * GPW + grp;
     const bool live = s < n_rows;
-    const uint32_t lane_bytes = (sub * V < ld_t) ? sub * 16u : 0u;
+    const uint32_t lane_bytes = (sub * V < cols) ? sub * 16u : 0u;
     const uint32_t row_bytes = (uint32_t)ld_t * (uint32_t)sizeof(TIn);
     int64_t beg = 0, end = 0;
     int r = 0;
@@ -226,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
             }
         }
     }
-    if (live && sub * V < ld_out) {
+    if (live && sub * V < cols) {
         float a[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) a[i] = acc0[i] + acc1[i];
@@ -241,7 +221,7 @@ inline bool narrow_ok(const SpmmArgs &a, size_t elem) {
 
 template <typename TIn, typename TOut, int LPR, int UW, int UG>
 int launch(const SpmmArgs &a, hipStream_t st) {
-    Epi ep{a.epilogue, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
+    Epi ep{a.epilogue == kEpiRelu ? kActRelu : kActNone, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
     const bool narrow = narrow_ok(a, sizeof(TIn));
     const int zero_row = (int)a.n;
     const TIn *t = static_cast<const TIn *>(a.t);
@@ -252,10 +232,10 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
             k_spmm_wave<TIn, TOut, LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, nblocks, ep);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep);
         else
             k_spmm_wave<TIn, TOut, LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, nblocks, ep);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep);
         GCN_LAUNCH_CHECK();
     }
     const int64_t n_light = a.n - a.n_heavy;
@@ -265,10 +245,12 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
             k_spmm_group<TIn, TOut, LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, nblocks, ep);
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
+                ep);
         else
             k_spmm_group<TIn, TOut, LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, nblocks, ep);
+                a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
+                ep);
         GCN_LAUNCH_CHECK();
     }
     return GCN_OK;
@@ -276,7 +258,7 @@ int launch(const SpmmArgs &a, hipStream_t st) {
 
 template <typename TIn, typename TOut>
 int launch_by_width(const SpmmArgs &a, hipStream_t st) {
-    const int pieces = (a.ld_t + Piece<TIn>::kElems - 1) / Piece<TIn>::kElems;   // 16-byte pieces per row
+    const int pieces = (a.cols + Piece<TIn>::kElems - 1) / Piece<TIn>::kElems;   // 16-byte pieces per row
     if (pieces <= 4) return launch<TIn, TOut, 4, 2, 4>(a, st);
     if (pieces <= 8) return launch<TIn, TOut, 8, 2, 8>(a, st);
     if (pieces <= 16) return launch<TIn, TOut, 16, 4, 8>(a, st);
@@ -289,8 +271,8 @@ int launch_by_width(const SpmmArgs &a, hipStream_t st) {
 int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     if (a.n <= 0) return GCN_OK;
     const int v_in = a.t_dtype == GCN_BF16 ? 8 : 4;
-    if (a.ld_t % 8 != 0 || a.ld_out % 8 != 0 || a.ld_out > a.ld_t || a.ld_t > 64 * v_in || a.n_heavy < 0 ||
-        a.n_heavy > a.n || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
+    if (a.ld_t % 8 != 0 || a.ld_out % 8 != 0 || a.cols % 8 != 0 || a.cols < 8 || a.cols > a.ld_t || a.cols > a.ld_out ||
+        a.cols > 64 * v_in || a.n_heavy < 0 || a.n_heavy > a.n || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
         set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld, types %d -> %d)", a.ld_t, a.ld_out,
                   (long long)a.n_heavy, (long long)a.n, a.t_dtype, a.out_dtype);
         return GCN_EINVAL;

@@ -310,3 +310,32 @@ def test_config_c5_full_size_bf16(B, oracle, capsys):
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True, say=lambda t: _say(capsys, "c5: oracle " + t))
     _say(capsys, "c5: comparing")
     H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
+
+
+# ------------------------------------------------------------------ layer 1 from the cached A_hat X
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ["partition_602_to_128", "rmat_100_to_256_3layers", "chung_lu_dropout"])
+def test_first_layer_from_cached_aggregate(B, oracle, case, dtype_name):
+    bf = dtype_name == "bf16"
+    dtype = B.GCN_BF16 if bf else B.GCN_F32
+    rtol = H.RTOL_BF16 if bf else H.RTOL_F32
+    p = 0.0
+    if case == "partition_602_to_128":
+        wl = workloads.reddit_partition(scale=0.08)     # 602 columns: the cached product is built in three column slabs
+    elif case == "rmat_100_to_256_3layers":
+        wl = workloads.rmat_large(scale=0.004)
+    else:
+        wl = workloads.chung_lu_mid(scale=0.05)
+        p = 0.3
+        # inverted dropout multiplies kept values, and their rounding errors, by 1/(1-p) but the rms of the
+        # tensor (a fraction p of it zeroed) only by 1/sqrt(1-p): the bfloat16 bound scales with the ratio
+        if bf:
+            rtol = rtol / np.sqrt(1.0 - p)
+    g = H.gpu_graph(B, wl, dtype=dtype)
+    results = {}
+    for mode in (0, 2):
+        _, gpu = H.gpu_epoch(B, g, wl, dtype=dtype, cache_ax=mode, dropout_p=p, seed=77)
+        _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=bf, dropout_p=p, seed=77)
+        H.compare_epoch(oracle, wl, gpu, tr, new, rtol=rtol)
+        results[mode] = gpu
+    assert results[0]["G"][0] is not None and results[2]["G"][0] is None
