@@ -135,7 +135,10 @@ def main() -> int:
             by = gather_bytes(E, n, w, esize)
             spmm["w%d" % w] = {"launches": cnt, "avg_ms": round(avg, 5), "gather_GBps": round(by / avg / 1e6, 1),
                                "alu_frac_fp32": round(2.0 * E * w / (avg * 1e-3) / (FP32_PEAK_TFLOPS * 1e12), 4)}
-    dom_w = wl.dims[1]
+    # dominant kernel: the widest aggregation that ran in the timed region (the width-d_1 one unless layer 1
+    # ran from the cached A_hat X, which leaves only the narrower ones)
+    timed = [w for w in widths if "w%d" % w in spmm]
+    dom_w = max(timed) if timed else wl.dims[1]
     roofline = None
     if "w%d" % dom_w in spmm:
         avg = spmm["w%d" % dom_w]["avg_ms"]

@@ -106,6 +106,19 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
  *     key = mix(mix(seed) ^ epoch * 0xD1B54A32D192ED03 ^ layer * 0x8CB92BA72F3D8DD7),
  * mix = the SplitMix64 output function, e = row * d_l + column, epoch = number of gcn_sgd_step
  * calls so far.  Weights start at zero; set them with gcn_set_weights.
+ *
+ * dtype must equal the graph's store_dtype.  With GCN_BF16, X, the hidden activations and the
+ * gradients flowing between kernels are stored as bfloat16 (round to nearest even); products run on
+ * bfloat16 matrix-core instructions with float32 accumulation; weights (master copy), weight
+ * gradients, logits, loss and every sum are float32.
+ *
+ * Order of the two products per layer (the result is the same, A_hat (H W) = (A_hat H) W): every layer
+ * is evaluated as A_hat (H W), except that layer 1 may be evaluated as (A_hat X) W_1 with P = A_hat X
+ * computed once in gcn_model_create, because X never changes: then neither the forward nor the backward
+ * pass of layer 1 needs an aggregation (dW_1 = P^T dZ_1).  The knob "cache_ax" (gcn_set_tunable, read by
+ * gcn_model_workspace_bytes and gcn_model_create) selects: 0 never, 1 (default) when dims[0] <= dims[1],
+ * 2 always; it needs n_layers >= 2 and costs two extra copies of X in the workspace.  In that mode
+ * GCN_T_G of layer 1 does not exist (gcn_get_tensor returns GCN_EINVAL for it).
  */
 int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes);
 int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype,

@@ -262,7 +262,12 @@ int launch_by_width(const SpmmArgs &a, hipStream_t st) {
     if (pieces <= 4) return launch<TIn, TOut, 4, 2, 4>(a, st);
     if (pieces <= 8) return launch<TIn, TOut, 8, 2, 8>(a, st);
     if (pieces <= 16) return launch<TIn, TOut, 16, 4, 8>(a, st);
-    if (pieces <= 32) return launch<TIn, TOut, 32, 8, 8>(a, st);
+    if (pieces <= 32) {
+        const int64_t u = tunable("spmm_u", 8);
+        if (u == 4) return launch<TIn, TOut, 32, 4, 8>(a, st);
+        if (u == 16) return launch<TIn, TOut, 32, 16, 8>(a, st);
+        return launch<TIn, TOut, 32, 8, 8>(a, st);
+    }
     return launch<TIn, TOut, 64, 8, 8>(a, st);
 }
 
