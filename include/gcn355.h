@@ -154,6 +154,19 @@ int gcn_backward(gcn_model *m, void *stream);
 /* W^l <- W^l - lr dW^l for all layers; advances the epoch counter.  Needs gcn_backward.  Asynchronous. */
 int gcn_sgd_step(gcn_model *m, float lr, void *stream);
 
+/* Adam step for all layers, the optimiser the paper trains KW-GCN with (Section 4.1: Adam, learning rate
+ * 0.02; it prints no other constant, the usual ones are beta1 = 0.9, beta2 = 0.999, eps = 1e-8):
+ *   m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+ *   W <- W - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps),   t = Adam steps so far + 1.
+ * The moments live in the model's workspace and are reset by gcn_set_weights.  Needs gcn_backward;
+ * advances the epoch counter like gcn_sgd_step.  Asynchronous. */
+int gcn_adam_step(gcn_model *m, float lr, float beta1, float beta2, float eps, void *stream);
+
+/* The same update on caller buffers [dev, count floats each]: w, the gradient dw, and the two moment
+ * arrays; `step` is t above (>= 1).  Asynchronous. */
+int gcn_adam_update(float *w, const float *dw, float *mom1, float *mom2, size_t count, float lr, float beta1,
+                    float beta2, float eps, int64_t step, void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Kernel timing for benchmarks: when enabled, every aggregation (SpMM) launch of the calls above is
  * bracketed by HIP events on the launch stream.  gcn_timing_read waits for the events and returns,

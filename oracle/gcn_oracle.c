@@ -292,3 +292,18 @@ int orc_loss_acc(int64_t n, int64_t classes, const double *logits, const int32_t
 void orc_sgd(int64_t count, double lr, const double *dW, double *W) {
     for (int64_t t = 0; t < count; ++t) W[t] -= lr * dW[t];
 }
+
+/* ---------------------------------------------------------------- Adam, the optimiser the paper trains KW-GCN with
+ * (Section 4.1: Adam, learning rate 0.02; the other constants are not printed, the defaults of the Adam
+ * paper are beta1 = 0.9, beta2 = 0.999, eps = 1e-8).  step counts from 1.
+ *   m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2 ;  W <- W - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps) */
+void orc_adam(int64_t count, double lr, double beta1, double beta2, double eps, int64_t step, const double *dW,
+              double *m, double *v, double *W) {
+    double c1 = 1.0 - pow(beta1, (double)step), c2 = 1.0 - pow(beta2, (double)step);
+    for (int64_t t = 0; t < count; ++t) {
+        double g = dW[t];
+        m[t] = beta1 * m[t] + (1.0 - beta1) * g;
+        v[t] = beta2 * v[t] + (1.0 - beta2) * g * g;
+        W[t] -= lr * (m[t] / c1) / (sqrt(v[t] / c2) + eps);
+    }
+}

@@ -66,6 +66,8 @@ def lib():
         L.orc_loss_acc.argtypes = [i64, i64, f64p, i32p, u8p, f64p, i64p, i64p, f64p]
         L.orc_sgd.argtypes = [i64, C.c_double, f64p, f64p]
         L.orc_sgd.restype = None
+        L.orc_adam.argtypes = [i64, C.c_double, C.c_double, C.c_double, C.c_double, i64, f64p, f64p, f64p, f64p]
+        L.orc_adam.restype = None
         _lib = L
     return _lib
 
@@ -249,6 +251,22 @@ def sgd(Ws, dWs, lr: float):
         W2 = _f64(W).copy()
         d = _f64(dW)
         lib().orc_sgd(W2.size, lr, _p(d, C.c_double), _p(W2, C.c_double))
+        out.append(W2)
+    return out
+
+
+def adam(Ws, dWs, state, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8):
+    """One Adam step on every layer.  state = {"t": steps so far, "m": [...], "v": [...]} (updated in place;
+    pass {} for a fresh optimiser).  -> new weights."""
+    if not state:
+        state.update(t=0, m=[np.zeros_like(_f64(W)) for W in Ws], v=[np.zeros_like(_f64(W)) for W in Ws])
+    state["t"] += 1
+    out = []
+    for l, (W, dW) in enumerate(zip(Ws, dWs)):
+        W2 = _f64(W).copy()
+        d = _f64(dW)
+        lib().orc_adam(W2.size, lr, beta1, beta2, eps, state["t"], _p(d, C.c_double), _p(state["m"][l], C.c_double),
+                       _p(state["v"][l], C.c_double), _p(W2, C.c_double))
         out.append(W2)
     return out
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "gcn_graph_get_csr", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
-    "gcn_calibration_copy", "gcn_set_tunable",
+    "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
 ]
 
 _lib = None
@@ -73,6 +73,8 @@ def lib():
         L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
         L.gcn_calibration_copy.argtypes = [vp, vp, sz, vp]
         L.gcn_set_tunable.argtypes = [C.c_char_p, i64]
+        L.gcn_adam_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float, vp]
+        L.gcn_adam_update.argtypes = [vp, vp, vp, vp, sz, C.c_float, C.c_float, C.c_float, C.c_float, i64, vp]
         for name in EXPORTS:
             if name != "gcn_last_error":
                 getattr(L, name).restype = C.c_int
@@ -260,3 +262,15 @@ def gcn_calibration_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
 
 def gcn_set_tunable(name: str, value: int) -> None:
     _check(lib().gcn_set_tunable(name.encode(), value))
+
+
+def gcn_adam_step(m: Model, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    _check(lib().gcn_adam_step(m.handle, lr, beta1, beta2, eps, _stream()))
+
+
+def gcn_adam_update(w: torch.Tensor, dw: torch.Tensor, mom1: torch.Tensor, mom2: torch.Tensor, lr: float, step: int,
+                    beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    n = w.numel()
+    assert dw.numel() == n and mom1.numel() == n and mom2.numel() == n
+    _check(lib().gcn_adam_update(_dev(w, torch.float32), _dev(dw, torch.float32), _dev(mom1, torch.float32),
+                                 _dev(mom2, torch.float32), n, lr, beta1, beta2, eps, step, _stream()))

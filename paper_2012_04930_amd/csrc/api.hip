@@ -99,6 +99,8 @@ struct Layer {
     void *h;     // n x ld_out : H_l (l < L) or the logits (l = L)
     void *dzs;   // (n + 1) x ld_out : D^-1/2 dLoss/dZ_l, row n zero
     void *g;     // n x ld_out : A_hat dLoss/dZ_l
+    float *am;   // Adam first moment, ld_in x ld_out
+    float *av;   // Adam second moment
     void *wb;    // bfloat16 mode: W as bfloat16, ld_in x ld_out
     void *wbt;   // bfloat16 mode: W^T as bfloat16, ld_out x ld_in
 };
@@ -110,6 +112,7 @@ struct gcn_model {
     std::vector<Layer> layers;
     float p = 0.f;
     uint64_t seed = 0, epoch = 0;
+    int64_t adam_steps = 0;
     float *partials = nullptr;
     size_t partial_floats = 0;
     double *loss_part = nullptr;
@@ -158,6 +161,8 @@ void carve_model(Carver &c, gcn_model &m) {
     for (auto &ly : m.layers) {
         ly.w = c.take<float>((size_t)ly.ld_in * ly.ld_out);
         ly.dw = c.take<float>((size_t)ly.ld_in * ly.ld_out);
+        ly.am = c.take<float>((size_t)ly.ld_in * ly.ld_out);
+        ly.av = c.take<float>((size_t)ly.ld_in * ly.ld_out);
         const size_t es = m.dtype == GCN_BF16 ? 2 : 4;
         const size_t act = (size_t)(n + 1) * ly.ld_out;
         ly.t = c.take<char>(act * es);
@@ -409,7 +414,7 @@ int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_
     m.l1_cached = want_l1_cached(n_layers, dims);
     for (int l = 0; l < n_layers; ++l)
         m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
-                                 nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
+                                 nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(nullptr);
     carve_model(c, m);
     *bytes = c.bytes();
@@ -455,7 +460,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     m->l1_cached = want_l1_cached(n_layers, dims);
     for (int l = 0; l < n_layers; ++l)
         m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
-                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
+                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(workspace);
     carve_model(c, *m);
     // zero everything once: padding columns, the extra zero rows and the weights start at zero
@@ -512,8 +517,13 @@ int gcn_set_weights(gcn_model *m, const float *flat, int on_host, void *stream) 
             int rc = weight_copies(ly.w, ly.ld_in, ly.ld_out, ly.wb, ly.wbt, ly.ld_in, st);
             if (rc) return rc;
         }
+        // new weights, fresh optimiser state
+        int rc = fill_zero(ly.am, (size_t)ly.ld_in * ly.ld_out * sizeof(float), st);
+        if (!rc) rc = fill_zero(ly.av, (size_t)ly.ld_in * ly.ld_out * sizeof(float), st);
+        if (rc) return rc;
         off += cnt;
     }
+    m->adam_steps = 0;
     m->have_forward = m->have_loss = m->have_backward = false;
     return GCN_OK;
 }
@@ -725,6 +735,36 @@ int gcn_sgd_step(gcn_model *m, float lr, void *stream) {
     m->epoch += 1;
     m->have_forward = m->have_loss = m->have_backward = false;
     return GCN_OK;
+}
+
+int gcn_adam_step(gcn_model *m, float lr, float beta1, float beta2, float eps, void *stream) {
+    if (!m || !m->have_backward) {
+        set_error("gcn_adam_step: call gcn_backward first");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (auto &ly : m->layers) {
+        int rc = adam_update(ly.w, ly.dw, ly.am, ly.av, (size_t)ly.ld_in * ly.ld_out, lr, beta1, beta2, eps,
+                             m->adam_steps + 1, st);
+        if (rc) return rc;
+        if (m->dtype == GCN_BF16) {
+            rc = weight_copies(ly.w, ly.ld_in, ly.ld_out, ly.wb, ly.wbt, ly.ld_in, st);
+            if (rc) return rc;
+        }
+    }
+    m->adam_steps += 1;
+    m->epoch += 1;
+    m->have_forward = m->have_loss = m->have_backward = false;
+    return GCN_OK;
+}
+
+int gcn_adam_update(float *w, const float *dw, float *mom1, float *mom2, size_t count, float lr, float beta1,
+                    float beta2, float eps, int64_t step, void *stream) {
+    if (!w || !dw || !mom1 || !mom2) {
+        set_error("gcn_adam_update: null pointer");
+        return GCN_EINVAL;
+    }
+    return adam_update(w, dw, mom1, mom2, count, lr, beta1, beta2, eps, step, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------------------------------- timing

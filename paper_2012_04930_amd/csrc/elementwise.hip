@@ -3,6 +3,8 @@
 // Task and metric: vertex classification scored by micro-F1, i.e. accuracy for one label per
 // vertex (Section 2.2).  The paper does not print its loss; this is the softmax cross-entropy of
 // the cited Kipf-Welling model, averaged over the train mask.  Update: plain SGD.
+#include <cmath>
+
 #include "common.hpp"
 #include "dtypes.hpp"
 
@@ -166,6 +168,20 @@ __global__ void k_sgd(float *__restrict__ w, const float *__restrict__ dw, size_
     if (t < count) w[t] = w[t] - lr * dw[t];
 }
 
+// Adam (Kingma & Ba): c1 = 1 - beta1^t, c2 = 1 - beta2^t are formed on the host in double precision.
+__global__ void k_adam(float *__restrict__ w, const float *__restrict__ dw, float *__restrict__ m,
+                       float *__restrict__ v, size_t count, float lr, float beta1, float beta2, float eps,
+                       float inv_c1, float inv_c2) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const float g = dw[t];
+    const float mt = beta1 * m[t] + (1.0f - beta1) * g;
+    const float vt = beta2 * v[t] + (1.0f - beta2) * g * g;
+    m[t] = mt;
+    v[t] = vt;
+    w[t] = w[t] - lr * (mt * inv_c1) / (sqrtf(vt * inv_c2) + eps);
+}
+
 // bfloat16 copies of a weight matrix w [rows x ld]: wb in the same layout, wbt transposed [ld x ld_t]
 __global__ void k_weight_copies(const float *__restrict__ w, int rows, int ld, bf16_t *__restrict__ wb,
                                 bf16_t *__restrict__ wbt, int ld_t) {
@@ -253,6 +269,20 @@ int loss_forward(int64_t n, int classes, const float *logits, int ld, const int3
     GCN_LAUNCH_CHECK();
     k_loss_final<<<dim3(1), dim3(kThreads), 0, st>>>(blocks, loss_part, corr_part, 1.0 / (double)n_train, result,
                                                      result_correct);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int adam_update(float *w, const float *dw, float *m, float *v, size_t count, float lr, float beta1, float beta2,
+                float eps, int64_t step, hipStream_t st) {
+    if (count == 0) return GCN_OK;
+    if (step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps > 0.0f)) {
+        set_error("adam: step must be >= 1, betas in [0, 1), eps > 0");
+        return GCN_EINVAL;
+    }
+    const double c1 = 1.0 - std::pow((double)beta1, (double)step), c2 = 1.0 - std::pow((double)beta2, (double)step);
+    k_adam<<<dim3(blocks_for((int64_t)count, kThreads)), dim3(kThreads), 0, st>>>(
+        w, dw, m, v, count, lr, beta1, beta2, eps, (float)(1.0 / c1), (float)(1.0 / c2));
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

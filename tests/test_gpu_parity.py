@@ -339,3 +339,52 @@ def test_first_layer_from_cached_aggregate(B, oracle, case, dtype_name):
         H.compare_epoch(oracle, wl, gpu, tr, new, rtol=rtol)
         results[mode] = gpu
     assert results[0]["G"][0] is not None and results[2]["G"][0] is None
+
+
+# ------------------------------------------------------------------ Adam
+def test_adam_update_kernel_matches_oracle(B, oracle):
+    count = 100_003
+    w0 = rng.normal_f32(21, 1, count) * 0.1
+    w = torch.from_numpy(w0.copy()).cuda()
+    m = torch.zeros(count, device="cuda")
+    v = torch.zeros(count, device="cuda")
+    state, ref = {}, [w0.astype(np.float64)]
+    # the C ABI carries lr, beta1, beta2, eps as float32: the oracle gets exactly those numbers
+    lr, b1, b2, eps = (float(np.float32(x)) for x in (0.02, 0.9, 0.999, 1e-8))
+    for t in range(1, 7):
+        g = rng.normal_f32(21, 10 + t, count) * (10.0 ** -(t % 4 + 2))      # magnitudes 1e-2 .. 1e-5
+        g[::97] = 0.0
+        B.gcn_adam_update(w, torch.from_numpy(g).cuda(), m, v, lr=0.02, step=t)
+        ref = oracle.adam(ref, [g], state, lr, b1, b2, eps)
+        H.assert_close(w.cpu().numpy(), ref[0], rtol=1e-5, what="weights after Adam step %d" % t)
+    H.assert_close(m.cpu().numpy(), state["m"][0], rtol=1e-5, what="first moment")
+    H.assert_close(v.cpu().numpy(), state["v"][0], rtol=1e-5, what="second moment")
+
+
+def test_training_with_adam_follows_the_oracle(B, oracle):
+    wl = workloads.chung_lu_mid(scale=0.05)
+    g = H.gpu_graph(B, wl)
+    m = B.gcn_model_create(g, wl.dims)
+    B.gcn_set_weights(m, wl.weights)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    ws = [w.astype(np.float64) for w in wl.weights]
+    state = {}
+    gpu_loss, ref_loss = [], []
+    lr, b1, b2, eps = (float(np.float32(x)) for x in (0.02, 0.9, 0.999, 1e-8))
+    for _e in range(6):
+        B.gcn_forward(m, True)
+        gpu_loss.append(B.gcn_loss_acc(m)[0])
+        B.gcn_backward(m)
+        B.gcn_adam_step(m, 0.02)
+        tr = oracle.backward(og, oracle.forward(og, wl.x, ws), ws, wl.labels, wl.mask)
+        ref_loss.append(tr.loss)
+        ws = oracle.adam(ws, tr.dW, state, lr, b1, b2, eps)
+    # Adam divides by sqrt(v): where a gradient entry is ~0 the quotient amplifies fp32-vs-fp64 differences, so
+    # weights are compared as a whole (relative Frobenius error) and by the share of entries within 1e-3
+    np.testing.assert_allclose(gpu_loss, ref_loss, rtol=2e-4)
+    assert gpu_loss[-1] < gpu_loss[0] - 0.05            # Adam at the paper's learning rate actually learns
+    for l in (1, 2):
+        got = B.gcn_get_tensor(m, B.GCN_T_W, l).cpu().numpy().astype(np.float64)
+        rel = np.linalg.norm(got - ws[l - 1]) / np.linalg.norm(ws[l - 1])
+        close = np.abs(got - ws[l - 1]) <= 1e-3 * np.maximum(np.abs(ws[l - 1]), np.sqrt(np.mean(ws[l - 1] ** 2)))
+        assert rel < 1e-3 and close.mean() > 0.999, (l, rel, close.mean())

@@ -344,3 +344,34 @@ def test_dropout_mask(oracle):
     assert np.all(tr.dZ[0][k == 0] == 0)
     tr_eval = oracle.forward(g, x, ws, p=0.5, training=False)
     np.testing.assert_allclose(tr_eval.H[1], np.maximum(tr_eval.Z[0], 0), rtol=0)
+
+
+# ------------------------------------------------------------------ Adam (the paper's optimiser, Section 4.1)
+def test_adam_closed_forms(oracle):
+    g = rng.normal_f32(3, 1, 60).reshape(12, 5).astype(np.float64)
+    w0 = rng.normal_f32(3, 2, 60).reshape(12, 5).astype(np.float64)
+    lr, eps = 0.02, 1e-8
+    # first step: bias correction makes m_hat = g and v_hat = g^2, so the move is lr * g / (|g| + eps)
+    st = {}
+    w1 = oracle.adam([w0], [g], st, lr)[0]
+    np.testing.assert_allclose(w0 - w1, lr * g / (np.abs(g) + eps), rtol=1e-12)
+    # a constant gradient keeps m_hat = g and v_hat = g^2 at every step: same move each time
+    w = w1
+    for _ in range(5):
+        w_next = oracle.adam([w], [g], st, lr)[0]
+        np.testing.assert_allclose(w - w_next, lr * g / (np.abs(g) + eps), rtol=1e-10)
+        w = w_next
+    assert st["t"] == 6
+    # zero gradient from the start: nothing moves (0 / (0 + eps))
+    st0 = {}
+    np.testing.assert_array_equal(oracle.adam([w0], [np.zeros_like(g)], st0, lr)[0], w0)
+    # textbook recurrences with numpy over a varying gradient sequence
+    st2, w, m, v = {}, w0.copy(), np.zeros_like(w0), np.zeros_like(w0)
+    b1, b2 = 0.9, 0.999
+    for t in range(1, 8):
+        gt = rng.normal_f32(9, t, 60).reshape(12, 5).astype(np.float64) * (0.1 * t)
+        m = b1 * m + (1 - b1) * gt
+        v = b2 * v + (1 - b2) * gt * gt
+        w = w - lr * (m / (1 - b1 ** t)) / (np.sqrt(v / (1 - b2 ** t)) + eps)
+        got = oracle.adam([w0 if t == 1 else got], [gt], st2, lr)[0]
+        np.testing.assert_allclose(got, w, rtol=1e-12, atol=1e-15)
