@@ -99,6 +99,34 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
                   size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Subgraph approximation: builds, on the GPU, the input the training step above runs on.
+ *
+ * gcn_augment_partition computes P_o[p] of Algorithm 1 (breadth-first random sampling, Section 3.1) for
+ * partition p of a graph whose vertices carry partition ids part[v] in [0, n_parts), and the subgraph it
+ * induces (Section 4: every edge between subgraphs that the sampling did not bring in is dropped).
+ *   nts = floor(overlap * N_p / (n_parts - 1)) vertices are wanted from each other partition op.
+ *   Level 1 of op = its vertices adjacent to p; level k + 1 = its vertices adjacent to level k and not seen
+ *   before.  Levels are taken whole while they fit; from the first that does not, exactly the missing
+ *   number is drawn; an empty level ends the search for op.
+ *   The paper names no random generator.  The draw keeps the vertices with the smallest
+ *   key(v) = mix(mix(seed) ^ v), mix = the SplitMix64 output function (a bijection: no ties).
+ * Inputs [dev]: rowptr (n + 1), col (nnz), part (n).  Outputs: *n_out, *n_local, *nnz_out [host];
+ * vertices [dev, capacity n]: old ids in new-id order — partition p ascending, then the sampled vertices
+ * ascending; rowptr_out [dev, capacity n + 1] and col_out [dev, capacity nnz]: raw CSR of the induced
+ * subgraph in new ids, entries of a row in the order of the input row (feed it to gcn_graph_create).
+ * Synchronous.  Errors: GCN_EGRAPH (bad CSR), GCN_EINVAL (partition id out of range ...), GCN_EWORKSPACE.
+ */
+int gcn_augment_workspace_bytes(int64_t n, size_t *bytes);
+int gcn_augment_partition(int64_t n, int64_t nnz, const int64_t *rowptr, const int32_t *col, const int32_t *part,
+                          int32_t n_parts, int32_t p, double overlap, uint64_t seed, void *workspace,
+                          size_t workspace_bytes, int64_t *n_out, int64_t *n_local, int64_t *nnz_out,
+                          int32_t *vertices, int64_t *rowptr_out, int32_t *col_out, void *stream);
+
+/* dst[i, :] = src[idx[i], :] for rows of row_bytes bytes (a multiple of 4): features, labels or masks of the
+ * vertices gcn_augment_partition lists.  All pointers [dev].  Asynchronous. */
+int gcn_gather_rows(const void *src, size_t row_bytes, const int32_t *idx, int64_t n_idx, void *dst, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Model: L layers of widths dims[0..L] (dims[0] = f, dims[L] = n_classes), one local copy of the
  * network as each worker holds it (Section 3.2).  dropout_p in [0, 1) applies to hidden activations
  * in training mode only; the keep mask is the integer function

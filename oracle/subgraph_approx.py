@@ -41,7 +41,9 @@ def sample_key(seed: int, v: int) -> int:
 
 
 def vertices_to_sample(overlap: float, n_p: int, n_parts: int) -> int:
-    """nts of Algorithm 1, line 2."""
+    """nts of Algorithm 1, line 2 (a single partition has no other partition to sample from)."""
+    if n_parts < 2:
+        return 0
     return int(np.floor(overlap * n_p / (n_parts - 1)))
 
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
     "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
+    "gcn_augment_workspace_bytes", "gcn_augment_partition", "gcn_gather_rows",
 ]
 
 _lib = None
@@ -73,6 +74,10 @@ def lib():
         L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
         L.gcn_calibration_copy.argtypes = [vp, vp, sz, vp]
         L.gcn_set_tunable.argtypes = [C.c_char_p, i64]
+        L.gcn_augment_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
+        L.gcn_augment_partition.argtypes = [i64, i64, vp, vp, vp, i32, i32, C.c_double, C.c_uint64, vp, sz,
+                                            C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), vp, vp, vp, vp]
+        L.gcn_gather_rows.argtypes = [vp, sz, vp, i64, vp, vp]
         L.gcn_adam_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float, vp]
         L.gcn_adam_update.argtypes = [vp, vp, vp, vp, sz, C.c_float, C.c_float, C.c_float, C.c_float, i64, vp]
         for name in EXPORTS:
@@ -274,3 +279,33 @@ def gcn_adam_update(w: torch.Tensor, dw: torch.Tensor, mom1: torch.Tensor, mom2:
     assert dw.numel() == n and mom1.numel() == n and mom2.numel() == n
     _check(lib().gcn_adam_update(_dev(w, torch.float32), _dev(dw, torch.float32), _dev(mom1, torch.float32),
                                  _dev(mom2, torch.float32), n, lr, beta1, beta2, eps, step, _stream()))
+
+
+def gcn_augment_partition(rowptr: torch.Tensor, col: torch.Tensor, part: torch.Tensor, n_parts: int, p: int,
+                          overlap: float, seed: int = 0):
+    """-> (vertices, n_local, rowptr_out, col_out): device tensors trimmed to their used length."""
+    L = lib()
+    n = rowptr.numel() - 1
+    nnz = col.numel()
+    need = C.c_size_t()
+    _check(L.gcn_augment_workspace_bytes(n, C.byref(need)))
+    ws = _workspace(need.value)
+    vertices = torch.empty(n, dtype=torch.int32, device="cuda")
+    rp = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+    cl = torch.empty(max(nnz, 1), dtype=torch.int32, device="cuda")
+    n_out, n_local, nnz_out = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(L.gcn_augment_partition(n, nnz, _dev(rowptr, torch.int64), _dev(col, torch.int32) if nnz else None,
+                                   _dev(part, torch.int32), n_parts, p, overlap, seed, ws.data_ptr(), ws.numel(),
+                                   C.byref(n_out), C.byref(n_local), C.byref(nnz_out), vertices.data_ptr(),
+                                   rp.data_ptr(), cl.data_ptr(), _stream()))
+    return vertices[:n_out.value], n_local.value, rp[:n_out.value + 1], cl[:nnz_out.value]
+
+
+def gcn_gather_rows(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    """src[idx] for a contiguous 1-D or 2-D tensor whose rows are a multiple of 4 bytes."""
+    assert src.is_cuda and src.is_contiguous() and idx.dtype == torch.int32
+    row_elems = src.shape[1] if src.dim() == 2 else 1
+    out = torch.empty((idx.numel(),) + tuple(src.shape[1:]), dtype=src.dtype, device="cuda")
+    _check(lib().gcn_gather_rows(src.data_ptr(), row_elems * src.element_size(), idx.data_ptr(), idx.numel(),
+                                 out.data_ptr(), _stream()))
+    return out

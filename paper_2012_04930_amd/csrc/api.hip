@@ -401,6 +401,57 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
 }
 
+// ------------------------------------------------------------------------------------------- subgraph approximation
+int gcn_augment_workspace_bytes(int64_t n, size_t *bytes) {
+    if (!bytes || n <= 0 || n >= 0x7ffffff0) {
+        set_error("gcn_augment_workspace_bytes: bad argument");
+        return GCN_EINVAL;
+    }
+    *bytes = augment_workspace_bytes(n);
+    return GCN_OK;
+}
+
+int gcn_augment_partition(int64_t n, int64_t nnz, const int64_t *rowptr, const int32_t *col, const int32_t *part,
+                          int32_t n_parts, int32_t p, double overlap, uint64_t seed, void *workspace,
+                          size_t workspace_bytes, int64_t *n_out, int64_t *n_local, int64_t *nnz_out,
+                          int32_t *vertices, int64_t *rowptr_out, int32_t *col_out, void *stream) {
+    if (!rowptr || (!col && nnz > 0) || !part || !n_out || !n_local || !nnz_out || !vertices || !rowptr_out ||
+        (!col_out && nnz > 0) || n <= 0 || n >= 0x7ffffff0 || nnz < 0 || n_parts < 1 || n_parts > 1024 || p < 0 ||
+        p >= n_parts || !(overlap >= 0.0)) {
+        set_error("gcn_augment_partition: null pointer or bad size (1 <= n_parts <= 1024, 0 <= p < n_parts, overlap >= 0)");
+        return GCN_EINVAL;
+    }
+    size_t need = augment_workspace_bytes(n);
+    if (!workspace || !aligned256(workspace) || workspace_bytes < need) {
+        set_error("gcn_augment_partition: workspace missing, misaligned or smaller than %zu bytes", need);
+        return GCN_EWORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // the same checks as for any graph: monotone row pointers, columns in range
+    int32_t *flags = (int32_t *)workspace;   // first words of the workspace, rewritten by the build below
+    int rc = fill_zero(flags, 16 * sizeof(int32_t), st);
+    if (rc) return rc;
+    rc = prep_validate(n, nnz, rowptr, col, flags, st);
+    if (rc) return rc;
+    int32_t host_flags[16];
+    GCN_HIP(hipMemcpyAsync(host_flags, flags, sizeof(host_flags), hipMemcpyDeviceToHost, st));
+    GCN_HIP(hipStreamSynchronize(st));
+    if (host_flags[0]) {
+        set_error("gcn_augment_partition: invalid CSR (%s)", (host_flags[0] & 1) ? "rowptr" : "column index out of range");
+        return GCN_EGRAPH;
+    }
+    return augment_partition(n, rowptr, col, part, n_parts, p, overlap, seed, workspace, n_out, n_local, nnz_out,
+                             vertices, rowptr_out, col_out, st);
+}
+
+int gcn_gather_rows(const void *src, size_t row_bytes, const int32_t *idx, int64_t n_idx, void *dst, void *stream) {
+    if (!src || !idx || !dst || n_idx < 0) {
+        set_error("gcn_gather_rows: null pointer or negative count");
+        return GCN_EINVAL;
+    }
+    return gather_rows(src, row_bytes, idx, n_idx, dst, (hipStream_t)stream);
+}
+
 // ------------------------------------------------------------------------------------------- model
 int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes) {
     if (!g || !bytes || check_dims(n_layers, dims) || (dtype != GCN_F32 && dtype != GCN_BF16)) {

@@ -86,6 +86,16 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
 int prep_labels_mask(int64_t n, const int32_t *labels, const uint8_t *mask, int32_t n_classes, int32_t *labels_out,
                      uint8_t *mask_out, int32_t *flags, hipStream_t st);
 size_t scan_blocks(int64_t n);
+// out[i] = in[0] + ... + in[i-1] for i = 0..n (n + 1 outputs); blocksum holds scan_blocks(n) words
+int exclusive_scan_i32(int64_t n, const int32_t *in, int64_t *out, int64_t *blocksum, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Subgraph approximation (augment.hip)
+size_t augment_workspace_bytes(int64_t n);
+int augment_partition(int64_t n, const int64_t *rowptr, const int32_t *col, const int32_t *part, int32_t n_parts,
+                      int32_t p, double overlap, uint64_t seed, void *workspace, int64_t *n_out, int64_t *n_local_out,
+                      int64_t *nnz_out, int32_t *vertices, int64_t *rowptr_out, int32_t *col_out, hipStream_t st);
+int gather_rows(const void *src, size_t row_bytes, const int32_t *idx, int64_t n_idx, void *dst, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
 // Layout helpers (elementwise.hip).  "padded" = row-major with leading dimension ld >= width, pad zero.

@@ -297,6 +297,10 @@ inline unsigned blocks_for(int64_t items, int per_block) { return (unsigned)((it
 
 size_t scan_blocks(int64_t n) { return (size_t)((n + kScanTile - 1) / kScanTile) + 2; }
 
+int exclusive_scan_i32(int64_t n, const int32_t *in, int64_t *out, int64_t *blocksum, hipStream_t st) {
+    return exclusive_scan(n, in, out, blocksum, st);
+}
+
 int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, int32_t *flags,
                   hipStream_t st) {
     k_validate_rowptr<<<dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, st>>>(n, nnz_in, rowptr, flags);

@@ -1,0 +1,109 @@
+"""GPU subgraph approximation (Algorithm 1 + edge dropping) vs its CPU oracle: bit-exact (run with -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import subgraph_approx as SA
+from synth import graphs, rng, workloads
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2012_04930_amd import binding
+    binding.lib()
+    return binding
+
+
+def _gpu_augment(B, rowptr, col, part, n_parts, p, overlap, seed):
+    v, n_local, rp, cl = B.gcn_augment_partition(torch.from_numpy(np.ascontiguousarray(rowptr, dtype=np.int64)).cuda(),
+                                                 torch.from_numpy(np.ascontiguousarray(col, dtype=np.int32)).cuda(),
+                                                 torch.from_numpy(np.ascontiguousarray(part, dtype=np.int32)).cuda(),
+                                                 n_parts, p, overlap, seed)
+    return v.cpu().numpy(), n_local, rp.cpu().numpy(), cl.cpu().numpy()
+
+
+def _check_against_oracle(B, n, rowptr, col, part, n_parts, p, overlap, seed):
+    want_v, want_nl, levels = SA.augmented_partition(n, rowptr, col, part, n_parts, p, overlap, seed)
+    want_rp, want_cl = SA.induced_subgraph(n, rowptr, col, want_v)
+    v, nl, rp, cl = _gpu_augment(B, rowptr, col, part, n_parts, p, overlap, seed)
+    assert nl == want_nl
+    np.testing.assert_array_equal(v, want_v)
+    np.testing.assert_array_equal(rp, want_rp)
+    np.testing.assert_array_equal(cl, want_cl)
+    return levels
+
+
+@pytest.mark.parametrize("n,n_parts,overlap,seed", [(200, 3, 0.3, 1), (500, 5, 0.1, 2), (300, 2, 0.9, 3),
+                                                    (400, 4, 2.5, 4), (64, 1, 0.5, 5), (300, 6, 0.0, 6)])
+def test_small_random_graphs_every_partition(B, n, n_parts, overlap, seed):
+    m = 3 * n
+    rowptr, col = graphs.erdos_renyi_gnm(n, m, seed)
+    part = rng.integers(seed, 50, n, n_parts).astype(np.int32)
+    for p in range(n_parts):
+        _check_against_oracle(B, n, rowptr, col, part, n_parts, p, overlap, seed)
+
+
+def test_sparse_graph_needs_several_levels(B):
+    # a long cycle cut into 4 arcs: each level adds two vertices per neighbouring arc, so nts = 10 needs 5+ levels
+    n = 400
+    rowptr, col = graphs.pairs_to_csr(n, np.arange(n), (np.arange(n) + 1) % n)
+    part = (np.arange(n) // 100).astype(np.int32)
+    levels = _check_against_oracle(B, n, rowptr, col, part, 4, 1, 0.3, seed=9)
+    assert len(levels[0]) >= 5 and len(levels[2]) >= 5 and levels[3] == []      # arc 3 does not touch arc 1
+
+
+def test_community_graph_with_partitions_of_communities(B):
+    wl = workloads.chung_lu_mid(scale=0.06)                  # 6,000 vertices, 20 communities of consecutive ids
+    part = (np.arange(wl.n) // (wl.n // 5)).clip(max=4).astype(np.int32)
+    for overlap in (0.1, 0.5):
+        for p in (0, 3):
+            _check_against_oracle(B, wl.n, wl.rowptr, wl.col, part, 5, p, overlap, seed=11)
+
+
+def test_bad_arguments(B):
+    n = 100
+    rowptr, col = graphs.erdos_renyi_gnm(n, 200, 1)
+    part = np.zeros(n, dtype=np.int32)
+    part[7] = 3
+    with pytest.raises(B.GcnError) as e:
+        _gpu_augment(B, rowptr, col, part, 3, 0, 0.1, 0)         # partition id 3 with n_parts = 3
+    assert e.value.code == -1
+    bad = col.copy()
+    bad[0] = n
+    with pytest.raises(B.GcnError) as e:
+        _gpu_augment(B, rowptr, bad, np.zeros(n, dtype=np.int32), 1, 0, 0.1, 0)
+    assert e.value.code == -2
+    torch.cuda.synchronize()
+
+
+def test_pipeline_augment_then_train(B, oracle):
+    """Whole method on one worker: partition a community graph, extend partition 2 by Algorithm 1 with a 10 %
+    overlap, drop the other cut edges, then one training epoch on the result; the oracle does the same on the
+    CPU, from the same full graph."""
+    wl = workloads.chung_lu_mid(scale=0.06)
+    n_parts, p, overlap, seed = 5, 2, 0.10, 3
+    part = (np.arange(wl.n) // (wl.n // n_parts)).clip(max=n_parts - 1).astype(np.int32)
+    d = H.to_dev(wl)
+    v, n_local, rp, cl = B.gcn_augment_partition(d["rowptr"], d["col"], torch.from_numpy(part).cuda(), n_parts, p,
+                                                 overlap, seed)
+    x = B.gcn_gather_rows(d["x"], v)
+    labels = B.gcn_gather_rows(d["labels"], v)
+    mask = torch.zeros(v.numel(), dtype=torch.uint8, device="cuda")
+    mask[:n_local] = torch.from_numpy(wl.mask[part == p]).cuda()         # sampled vertices stay outside the loss
+    g = B.gcn_graph_create(rp, cl, x, labels, mask, wl.dims[-1])
+    # the oracle's version of the same worker input
+    ov, onl, _ = SA.augmented_partition(wl.n, wl.rowptr, wl.col, part, n_parts, p, overlap, seed)
+    orp, ocl = SA.induced_subgraph(wl.n, wl.rowptr, wl.col, ov)
+    assert onl == n_local and len(ov) == v.numel() and len(ov) - onl == 4 * int(np.floor(overlap * onl / 4))
+    sub = workloads.Workload("partition %d with overlap" % p, len(ov), onl, orp, ocl, wl.x[ov], wl.labels[ov],
+                             np.concatenate([wl.mask[part == p], np.zeros(len(ov) - onl, dtype=np.uint8)]), wl.dims,
+                             wl.weights)
+    np.testing.assert_array_equal(x.cpu().numpy(), sub.x)
+    np.testing.assert_array_equal(labels.cpu().numpy(), sub.labels)
+    _, gpu = H.gpu_epoch(B, g, sub)
+    _, tr, new = H.oracle_epoch(oracle, sub, gpu=gpu)
+    H.compare_epoch(oracle, sub, gpu, tr, new)
