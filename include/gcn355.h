@@ -190,6 +190,13 @@ int gcn_sgd_step(gcn_model *m, float lr, void *stream);
  * advances the epoch counter like gcn_sgd_step.  Asynchronous. */
 int gcn_adam_step(gcn_model *m, float lr, float beta1, float beta2, float eps, void *stream);
 
+/* Parameter aggregation of Section 3.2: at the end of an epoch every worker's weights W_i are replaced by
+ * their average W_agg = (1 / n) sum_i W_i (summed in list order).  Here the n models (at most 64, same layer
+ * widths and storage type, typically one per partition) live on one GPU; across GPUs the same step is one
+ * all-reduce of the flat weight buffer.  Optimiser moments are left alone: the paper averages parameters.
+ * All models' work must be on, or ordered before, `stream`.  Asynchronous. */
+int gcn_average_weights(gcn_model *const *models, int32_t n_models, void *stream);
+
 /* The same update on caller buffers [dev, count floats each]: w, the gradient dw, and the two moment
  * arrays; `step` is t above (>= 1).  Asynchronous. */
 int gcn_adam_update(float *w, const float *dw, float *mom1, float *mom2, size_t count, float lr, float beta1,

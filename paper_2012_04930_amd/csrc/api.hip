@@ -809,6 +809,41 @@ int gcn_adam_step(gcn_model *m, float lr, float beta1, float beta2, float eps, v
     return GCN_OK;
 }
 
+int gcn_average_weights(gcn_model *const *models, int32_t n_models, void *stream) {
+    if (!models || n_models < 1 || n_models > 64) {
+        set_error("gcn_average_weights: between 1 and 64 models");
+        return GCN_EINVAL;
+    }
+    for (int i = 0; i < n_models; ++i) {
+        if (!models[i] || models[i]->L != models[0]->L || models[i]->dtype != models[0]->dtype) {
+            set_error("gcn_average_weights: model %d is null or of another shape", i);
+            return GCN_EINVAL;
+        }
+        for (int l = 0; l < models[0]->L; ++l)
+            if (models[i]->layers[l].d_in != models[0]->layers[l].d_in ||
+                models[i]->layers[l].d_out != models[0]->layers[l].d_out) {
+                set_error("gcn_average_weights: model %d has other layer widths", i);
+                return GCN_EINVAL;
+            }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (int l = 0; l < models[0]->L; ++l) {
+        float *ws[64];
+        for (int i = 0; i < n_models; ++i) ws[i] = models[i]->layers[l].w;
+        const Layer &ly = models[0]->layers[l];
+        int rc = average_in_place(ws, n_models, (size_t)ly.ld_in * ly.ld_out, st);
+        if (rc) return rc;
+        for (int i = 0; i < n_models && models[0]->dtype == GCN_BF16; ++i) {
+            Layer &li = models[i]->layers[l];
+            rc = weight_copies(li.w, li.ld_in, li.ld_out, li.wb, li.wbt, li.ld_in, st);
+            if (rc) return rc;
+        }
+    }
+    for (int i = 0; i < n_models; ++i)
+        models[i]->have_forward = models[i]->have_loss = models[i]->have_backward = false;
+    return GCN_OK;
+}
+
 int gcn_adam_update(float *w, const float *dw, float *mom1, float *mom2, size_t count, float lr, float beta1,
                     float beta2, float eps, int64_t step, void *stream) {
     if (!w || !dw || !mom1 || !mom2) {

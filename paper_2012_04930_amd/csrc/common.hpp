@@ -119,6 +119,8 @@ int loss_forward(int64_t n, int classes, const float *logits, int ld, const int3
 int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st);
 int adam_update(float *w, const float *dw, float *m, float *v, size_t count, float lr, float beta1, float beta2,
                 float eps, int64_t step, hipStream_t st);
+// every weights[i][0..elems) becomes the mean over i (summed in list order)
+int average_in_place(float *const *weights, int count, size_t elems, hipStream_t st);
 int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------

@@ -182,6 +182,20 @@ __global__ void k_adam(float *__restrict__ w, const float *__restrict__ dw, floa
     w[t] = w[t] - lr * (mt * inv_c1) / (sqrtf(vt * inv_c2) + eps);
 }
 
+// dst[t] = (1 / count) * sum over the models, in list order, of srcs[i][t]; then every model gets dst.
+struct AverageList {
+    float *w[64];
+    int count;
+};
+__global__ void k_average(AverageList list, size_t elems) {
+    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= elems) return;
+    float s = 0.0f;
+    for (int i = 0; i < list.count; ++i) s += list.w[i][t];
+    s *= 1.0f / (float)list.count;
+    for (int i = 0; i < list.count; ++i) list.w[i][t] = s;
+}
+
 // bfloat16 copies of a weight matrix w [rows x ld]: wb in the same layout, wbt transposed [ld x ld_t]
 __global__ void k_weight_copies(const float *__restrict__ w, int rows, int ld, bf16_t *__restrict__ wb,
                                 bf16_t *__restrict__ wbt, int ld_t) {
@@ -283,6 +297,20 @@ int adam_update(float *w, const float *dw, float *m, float *v, size_t count, flo
     const double c1 = 1.0 - std::pow((double)beta1, (double)step), c2 = 1.0 - std::pow((double)beta2, (double)step);
     k_adam<<<dim3(blocks_for((int64_t)count, kThreads)), dim3(kThreads), 0, st>>>(
         w, dw, m, v, count, lr, beta1, beta2, eps, (float)(1.0 / c1), (float)(1.0 / c2));
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int average_in_place(float *const *weights, int count, size_t elems, hipStream_t st) {
+    if (count < 1 || count > 64) {
+        set_error("parameter averaging: between 1 and 64 models");
+        return GCN_EINVAL;
+    }
+    if (elems == 0) return GCN_OK;
+    AverageList list;
+    list.count = count;
+    for (int i = 0; i < count; ++i) list.w[i] = weights[i];
+    k_average<<<dim3(blocks_for((int64_t)elems, kThreads)), dim3(kThreads), 0, st>>>(list, elems);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -107,3 +107,45 @@ def test_pipeline_augment_then_train(B, oracle):
     _, gpu = H.gpu_epoch(B, g, sub)
     _, tr, new = H.oracle_epoch(oracle, sub, gpu=gpu)
     H.compare_epoch(oracle, sub, gpu, tr, new)
+
+
+def test_workers_train_then_average_parameters(B, oracle):
+    """Section 3.2 on one GPU: three workers, each with its own augmented partition and its own copy of the
+    network, train one epoch from the same weights; the parameter server step replaces every copy by the mean."""
+    wl = workloads.chung_lu_mid(scale=0.045)
+    n_parts, overlap, seed = 3, 0.2, 5
+    part = (np.arange(wl.n) // (wl.n // n_parts)).clip(max=n_parts - 1).astype(np.int32)
+    d = H.to_dev(wl)
+    part_dev = torch.from_numpy(part).cuda()
+    models, graphs_, ref_new = [], [], []
+    for p in range(n_parts):
+        v, n_local, rp, cl = B.gcn_augment_partition(d["rowptr"], d["col"], part_dev, n_parts, p, overlap, seed)
+        mask = torch.zeros(v.numel(), dtype=torch.uint8, device="cuda")
+        mask[:n_local] = torch.from_numpy(wl.mask[part == p]).cuda()
+        g = B.gcn_graph_create(rp, cl, B.gcn_gather_rows(d["x"], v), B.gcn_gather_rows(d["labels"], v), mask,
+                               wl.dims[-1])
+        m = B.gcn_model_create(g, wl.dims)
+        B.gcn_set_weights(m, wl.weights)
+        B.gcn_forward(m, True)
+        B.gcn_loss_acc(m, sync=False)
+        B.gcn_backward(m)
+        B.gcn_sgd_step(m, wl.lr)
+        models.append(m)
+        graphs_.append(g)
+        ov, onl, _ = SA.augmented_partition(wl.n, wl.rowptr, wl.col, part, n_parts, p, overlap, seed)
+        orp, ocl = SA.induced_subgraph(wl.n, wl.rowptr, wl.col, ov)
+        og = oracle.canonicalise(len(ov), orp, ocl)
+        omask = np.concatenate([wl.mask[part == p], np.zeros(len(ov) - onl, dtype=np.uint8)])
+        new, _ = oracle.train_epoch(og, wl.x[ov], [w.astype(np.float64) for w in wl.weights], wl.labels[ov], omask,
+                                    wl.lr)
+        ref_new.append(new)
+    B.gcn_average_weights(models)
+    for l in (1, 2):
+        want = np.mean([rn[l - 1] for rn in ref_new], axis=0)
+        got = [B.gcn_get_tensor(m, B.GCN_T_W, l).cpu().numpy() for m in models]
+        for gw in got:
+            H.assert_close(gw, want, what="averaged W%d" % l)
+            np.testing.assert_array_equal(gw, got[0])            # every worker holds the same bits afterwards
+    # training continues from the aggregate
+    B.gcn_forward(models[0], True)
+    assert np.isfinite(B.gcn_loss_acc(models[0])[0])
