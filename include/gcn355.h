@@ -216,6 +216,10 @@ int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
  * are stored and ignored. */
 int gcn_set_tunable(const char *name, int64_t value);
 
+/* Measurement aid: launches n_blocks workgroups of 256 threads and writes, for each, the id of the XCD it ran on
+ * (out [dev, n_blocks int32]).  The aggregation kernels assume that workgroup b runs on XCD b mod 8. */
+int gcn_xcc_ids(int32_t *out, int32_t n_blocks, void *stream);
+
 /* Measurement aid: copies `bytes` (a multiple of 16) from src to dst [dev] with one plain streaming
  * kernel (k_calibration_copy), which reads and writes exactly `bytes` each.  Hardware byte counters
  * collected for the library's kernels are scaled by what they report for this one.  Asynchronous. */

@@ -27,7 +27,7 @@ EXPORTS = [
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
     "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
-    "gcn_augment_workspace_bytes", "gcn_augment_partition", "gcn_gather_rows", "gcn_average_weights",
+    "gcn_augment_workspace_bytes", "gcn_augment_partition", "gcn_gather_rows", "gcn_average_weights", "gcn_xcc_ids",
 ]
 
 _lib = None
@@ -78,6 +78,7 @@ def lib():
         L.gcn_augment_partition.argtypes = [i64, i64, vp, vp, vp, i32, i32, C.c_double, C.c_uint64, vp, sz,
                                             C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), vp, vp, vp, vp]
         L.gcn_gather_rows.argtypes = [vp, sz, vp, i64, vp, vp]
+        L.gcn_xcc_ids.argtypes = [vp, i32, vp]
         L.gcn_average_weights.argtypes = [C.POINTER(vp), i32, vp]
         L.gcn_adam_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float, vp]
         L.gcn_adam_update.argtypes = [vp, vp, vp, vp, sz, C.c_float, C.c_float, C.c_float, C.c_float, i64, vp]
@@ -315,3 +316,9 @@ def gcn_gather_rows(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
 def gcn_average_weights(models) -> None:
     arr = (C.c_void_p * len(models))(*[m.handle for m in models])
     _check(lib().gcn_average_weights(arr, len(models), _stream()))
+
+
+def gcn_xcc_ids(n_blocks: int) -> torch.Tensor:
+    out = torch.empty(n_blocks, dtype=torch.int32, device="cuda")
+    _check(lib().gcn_xcc_ids(out.data_ptr(), n_blocks, _stream()))
+    return out

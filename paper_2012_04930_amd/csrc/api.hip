@@ -138,6 +138,32 @@ uint64_t host_mix64(uint64_t z) {
 
 bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
+SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
+                   int cols, int width, int epilogue) {
+    SpmmArgs a{};
+    a.rowptr = g->pb.rowptr;
+    a.col = g->pb.col;
+    a.perm = g->pb.perm;
+    a.dinv = g->pb.dinv;
+    a.segoff = g->pb.segoff;
+    a.prow = g->pb.prow;
+    a.n = g->n;
+    a.n_heavy = g->n_heavy;
+    a.t = t;
+    a.t_dtype = t_dtype;
+    a.ld_t = ld_t;
+    a.out = out;
+    a.out_dtype = out_dtype;
+    a.ld_out = ld_out;
+    a.cols = cols;
+    a.width = width;
+    a.epilogue = epilogue;
+    a.drop_threshold = 0u;
+    a.keep_scale = 1.0f;
+    a.drop_key = 0ull;
+    return a;
+}
+
 void carve_graph(Carver &c, gcn_graph &g) {
     const int64_t n = g.n, cap = g.nnz_in + n;
     g.pb.rowptr = c.take<int64_t>(n + 1);
@@ -148,6 +174,9 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.scratch = c.take<int32_t>(cap);
     g.pb.heavy = c.take<int32_t>(n);
     g.pb.hpos = c.take<int64_t>(n + 1);
+    g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
+    int pw = 0, pr = 0;
+    g.pb.prow = phased_shape(n, &pw, &pr) ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
     g.pb.flags = c.take<int32_t>(16);
     g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
@@ -306,6 +335,10 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
 
     FAIL_IF(prep_canonical(n, nnz_in, rowptr, col, g->pb, st));
     FAIL_IF(prep_schedule(n, g->pb, st));
+    {
+        int pw = 0, pr = 0;
+        if (g->pb.prow && phased_shape(n, &pw, &pr)) FAIL_IF(prep_balance_rows(n, g->pb.deg, pw, pr, g->pb.prow, st));
+    }
     const size_t x_es = store_dtype == GCN_BF16 ? 2 : 4;
     FAIL_IF(pad_rows(feat, n, f, g->x, store_dtype, g->ldf, nullptr, st));
     FAIL_IF(fill_zero((char *)g->x + (size_t)n * g->ldf * x_es, (size_t)g->ldf * x_es, st));
@@ -394,8 +427,7 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     if (rc) return rc;
     rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
     if (rc) return rc;
-    SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, t, dtype, ld, z, GCN_F32, ld, ld, width,
-               kEpiNone, 0u, 1.0f, 0ull};
+    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone);
     rc = spmm_launch(a, st);
     if (rc) return rc;
     return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
@@ -524,8 +556,8 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
         const size_t es = dtype == GCN_BF16 ? 2 : 4;
         for (int c0 = 0; !rc && c0 < g->ldf; c0 += slab) {
             const int cols = g->ldf - c0 < slab ? g->ldf - c0 : slab;
-            SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, (const char *)m->xs + c0 * es,
-                       dtype, g->ldf, (char *)m->pax + c0 * es, dtype, g->ldf, cols, g->f, kEpiNone, 0u, 1.0f, 0ull};
+            SpmmArgs a = spmm_args(g, (const char *)m->xs + c0 * es, dtype, g->ldf, (char *)m->pax + c0 * es, dtype,
+                                   g->ldf, cols, g->f, kEpiNone);
             rc = spmm_launch(a, st);
         }
     }
@@ -659,9 +691,11 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
                               ly.ld_out, g->pb.dinv, nullptr, st);
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
-        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.t, m->dtype, ly.ld_out, ly.h,
-                   l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out, ly.d_out, l < m->L ? kEpiRelu : kEpiNone,
-                   act.drop_threshold, act.keep_scale, act.drop_key};
+        SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
+                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone);
+        a.drop_threshold = act.drop_threshold;
+        a.keep_scale = act.keep_scale;
+        a.drop_key = act.drop_key;
         rc = spmm_launch(a, st);
         if (rc) return rc;
         h_prev = ly.h;
@@ -737,8 +771,7 @@ int gcn_backward(gcn_model *m, void *stream) {
             continue;
         }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
-        SpmmArgs a{g->pb.rowptr, g->pb.col, g->pb.perm, g->pb.dinv, g->n, g->n_heavy, ly.dzs, m->dtype, ly.ld_out, ly.g,
-                   m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone, 0u, 1.0f, 0ull};
+        SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone);
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G
@@ -867,6 +900,14 @@ int gcn_set_tunable(const char *name, int64_t value) {
         }
     g_knobs.push_back({std::string(name), value});
     return GCN_OK;
+}
+
+int gcn_xcc_ids(int32_t *out, int32_t n_blocks, void *stream) {
+    if (!out || n_blocks < 0) {
+        set_error("gcn_xcc_ids: null pointer or negative count");
+        return GCN_EINVAL;
+    }
+    return xcc_ids(out, n_blocks, (hipStream_t)stream);
 }
 
 int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream) {

@@ -40,6 +40,7 @@ constexpr int kWave = 64;
 constexpr int kLdAlign = 16;   // leading dimensions are multiples of 16 elements (64 B in fp32)
 constexpr int kColSlack = 64;  // readable entries after the last column index (index prefetch runs one step ahead)
 constexpr int kHeavyDegree = 32;  // rows with at least this many entries get a whole wave in the aggregation
+constexpr int kColBlocks = 8;     // column ranges of the phased aggregation schedule, one per XCD
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -70,6 +71,11 @@ struct PrepBuffers {
     float *dinv;       // n
     // schedule: heavy rows (degree >= kHeavyDegree) first, then light rows, each in ascending vertex order
     int32_t *perm;     // n   slot -> row
+    // column blocks: the ids are cut into kColBlocks equal ranges; segoff[r * (kColBlocks + 1) + b] is the offset,
+    // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
+    int32_t *segoff;   // n * (kColBlocks + 1)
+    // phased schedule (only for graphs small enough for it, else unused): rows of each wave, see phased_shape()
+    int32_t *prow;     // kColBlocks * W * R
     // scratch
     int32_t *scratch;  // nnz_in + n
     int32_t *heavy;    // n   1 if the row is heavy
@@ -83,6 +89,18 @@ int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_
 int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, PrepBuffers &pb,
                    hipStream_t st);
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
+// Phased aggregation schedule: each XCD owns one of kColBlocks id ranges, each of its W waves R rows.
+// false when the graph is too large for it: more than 8 rows per wave with 896 waves per XCD (32 CUs x 4 SIMDs x
+// 7 waves, what the kernel's register use lets be resident at once; the schedule wants the whole grid resident).
+inline bool phased_shape(int64_t n, int *W, int *R) {
+    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+    const int64_t need = (block + 895) / 896;
+    if (need > 8) return false;
+    *R = need <= 4 ? 4 : (need <= 6 ? 6 : 8);
+    *W = (int)((block + *R - 1) / *R);
+    return true;
+}
+int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st);
 int prep_labels_mask(int64_t n, const int32_t *labels, const uint8_t *mask, int32_t n_classes, int32_t *labels_out,
                      uint8_t *mask_out, int32_t *flags, hipStream_t st);
 size_t scan_blocks(int64_t n);
@@ -122,6 +140,7 @@ int adam_update(float *w, const float *dw, float *m, float *v, size_t count, flo
 // every weights[i][0..elems) becomes the mean over i (summed in list order)
 int average_in_place(float *const *weights, int count, size_t elems, hipStream_t st);
 int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+int xcc_ids(int32_t *out, int n_blocks, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
 // Aggregation (spmm.hip):  out[r, :] = dinv[r] * sum over the columns c of row r of  t[c, :],
@@ -134,6 +153,8 @@ struct SpmmArgs {
     const int32_t *col;     // kColSlack readable entries follow the last one
     const int32_t *perm;
     const float *dinv;
+    const int32_t *segoff;  // column-block offsets per row (see PrepBuffers)
+    const int32_t *prow;    // rows per wave of the phased schedule, or null
     int64_t n;
     int64_t n_heavy;
     const void *t;      // float or bfloat16, ld_t elements per row, n + 1 rows

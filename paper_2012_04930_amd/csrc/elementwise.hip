@@ -157,6 +157,11 @@ __global__ __launch_bounds__(kThreads) void k_loss_final(int parts, const double
     }
 }
 
+// Which XCD each workgroup of a launch runs on: the XCC_ID hardware register (low 4 bits), read with s_getreg.
+__global__ void k_xcc_ids(int32_t *__restrict__ out) {
+    if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+}
+
 // Plain streaming copy of 16-byte words: the known-size kernel hardware byte counters are scaled by.
 __global__ void k_calibration_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t words) {
     size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -311,6 +316,13 @@ int average_in_place(float *const *weights, int count, size_t elems, hipStream_t
     list.count = count;
     for (int i = 0; i < count; ++i) list.w[i] = weights[i];
     k_average<<<dim3(blocks_for((int64_t)elems, kThreads)), dim3(kThreads), 0, st>>>(list, elems);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int xcc_ids(int32_t *out, int n_blocks, hipStream_t st) {
+    if (n_blocks <= 0) return GCN_OK;
+    k_xcc_ids<<<dim3(n_blocks), dim3(kThreads), 0, st>>>(out);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -275,6 +275,69 @@ __global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const
     if (i == 0) flags[4] = (int32_t)n_heavy;
 }
 
+// One wave per row: lane b (0..kColBlocks) finds, by bisection in the sorted row, the offset of the first column
+// that is >= b * block (block = ids per column range); lane kColBlocks gets the row length.
+__global__ __launch_bounds__(kThreads) void k_segment_offsets(int64_t n, const int64_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ col, int64_t block,
+                                                              int32_t *__restrict__ segoff) {
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (r >= n || lane > kColBlocks) return;
+    const int64_t beg = rowptr[r], end = rowptr[r + 1];
+    int64_t lo = beg, hi = end;
+    if (lane < kColBlocks) {
+        const int64_t bound = (int64_t)lane * block;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)col[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+    } else {
+        lo = end;
+    }
+    segoff[r * (kColBlocks + 1) + lane] = (int32_t)(lo - beg);
+}
+
+// Phased schedule: which rows each wave of XCD x owns.  One workgroup per id range x: sorts the range's rows by
+// degree (descending, ties by id) in LDS, then deals them to W waves in serpentine order, R per wave, so that every
+// wave carries nearly the same number of entries: prow[(x * W + q) * R + j] = row (or -1).
+constexpr int kMaxRangeRows = 8192;
+__global__ __launch_bounds__(kThreads) void k_balance_rows(int64_t n, int64_t block, const int32_t *__restrict__ deg,
+                                                           int W, int R, int32_t *__restrict__ prow) {
+    __shared__ unsigned long long key[kMaxRangeRows];
+    const int x = blockIdx.x;
+    const int64_t lo = (int64_t)x * block;
+    const int64_t hi = lo + block < n ? lo + block : n;
+    const int m = hi > lo ? (int)(hi - lo) : 0;
+    int P = 2;
+    while (P < m) P <<= 1;
+    // ascending sort of (~degree, id): largest degree first, smaller id first among equals; padding sorts last
+    for (int t = threadIdx.x; t < P; t += kThreads)
+        key[t] = t < m ? (((unsigned long long)(0x7fffffffu - (unsigned)deg[lo + t])) << 32) | (unsigned)(lo + t)
+                       : ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < P; t += kThreads) {
+                int y = t ^ j;
+                if (y > t) {
+                    unsigned long long a = key[t], c = key[y];
+                    bool up = (t & k) == 0;
+                    if (up ? (a > c) : (a < c)) {
+                        key[t] = c;
+                        key[y] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int idx = threadIdx.x; idx < W * R; idx += kThreads) {
+        const int q = idx / R, j = idx % R;
+        const int rank = (j & 1) ? j * W + (W - 1 - q) : j * W + q;
+        prow[((int64_t)x * W + q) * R + j] = rank < m ? (int32_t)(key[rank] & 0xffffffffu) : -1;
+    }
+}
+
 __global__ void k_labels_mask(int64_t n, const int32_t *__restrict__ labels, const uint8_t *__restrict__ mask,
                               int32_t n_classes, int32_t *__restrict__ labels_out, uint8_t *__restrict__ mask_out,
                               int32_t *flags) {
@@ -335,6 +398,21 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     int rc = exclusive_scan(n, pb.heavy, pb.hpos, pb.blocksum, st);
     if (rc) return rc;
     k_place_rows<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.heavy, pb.hpos, pb.perm, pb.flags);
+    GCN_LAUNCH_CHECK();
+    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+    k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,
+                                                                                      pb.segoff);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
+int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st) {
+    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+    if (block > kMaxRangeRows) {
+        set_error("phased schedule: more than %d rows per range", kMaxRangeRows);
+        return GCN_EINVAL;
+    }
+    k_balance_rows<<<dim3(kColBlocks), dim3(kThreads), 0, st>>>(n, block, deg, W, R, prow);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

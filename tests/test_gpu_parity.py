@@ -388,3 +388,35 @@ def test_training_with_adam_follows_the_oracle(B, oracle):
         rel = np.linalg.norm(got - ws[l - 1]) / np.linalg.norm(ws[l - 1])
         close = np.abs(got - ws[l - 1]) <= 1e-3 * np.maximum(np.abs(ws[l - 1]), np.sqrt(np.mean(ws[l - 1] ** 2)))
         assert rel < 1e-3 and close.mean() > 0.999, (l, rel, close.mean())
+
+
+# ------------------------------------------------------------------ phased aggregation schedule
+@pytest.mark.parametrize("width", [24, 41, 64, 128])
+@pytest.mark.parametrize("bf", [False, True], ids=["f32", "bf16"])
+def test_phased_schedule_matches_oracle_and_the_plain_schedule(B, oracle, width, bf):
+    wl = workloads.reddit_partition(scale=0.1)          # 4.7 k vertices, every row has >= 32 entries
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    assert og.deg.min() >= 32
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(width, 3, wl.n * width).reshape(wl.n, width)
+    xd = torch.from_numpy(x).cuda()
+    dtype = B.GCN_BF16 if bf else B.GCN_F32
+    out = {}
+    for knob in (0, 1):
+        B.gcn_set_tunable("spmm_phased", knob)
+        try:
+            out[knob] = B.gcn_aggregate(g, xd, dtype=dtype).cpu().numpy()
+        finally:
+            B.gcn_set_tunable("spmm_phased", -1)
+    ref = oracle.aggregate(og, x)
+    for knob in (0, 1):
+        H.assert_close(out[knob], ref, rtol=H.RTOL_BF16 if bf else H.RTOL_F32, what="schedule %d" % knob)
+    # same terms, another order of summation: the two schedules agree to rounding
+    np.testing.assert_allclose(out[1], out[0], rtol=0, atol=3e-6 * np.abs(ref).max() * (300 if bf else 1))
+
+
+def test_workgroups_are_dealt_round_robin_over_the_xcds(B):
+    """The aggregation kernels give XCD b mod 8 one contiguous range of rows; that rests on this dispatch order."""
+    for nb in (64, 1488, 20000):
+        ids = B.gcn_xcc_ids(nb).cpu().numpy()
+        np.testing.assert_array_equal(ids, np.arange(nb) % 8)
