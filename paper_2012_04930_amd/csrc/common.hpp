@@ -129,7 +129,7 @@ int fill_zero(void *p, size_t bytes, hipStream_t st);
 int scale_rows(const void *src, void *dst, int dtype, int64_t rows, int ld, const float *rowscale, hipStream_t st);
 
 // Loss / accuracy / dLoss/dlogits (scaled by dinv for the aggregation that follows).
-constexpr int kLossBlocks = 512;
+constexpr int kLossBlocks = 4096;
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
                  const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
                  long long *corr_part, float *result /* [0] loss, [1] accuracy, as float */,
