@@ -143,7 +143,7 @@ def main() -> int:
     if "w%d" % dom_w in spmm:
         avg = spmm["w%d" % dom_w]["avg_ms"]
         achieved = gather_bytes(E, n, dom_w, esize) / avg / 1e6
-        roofline = {"bound": "hbm", "kernel": "aggregation (k_spmm_wave + k_spmm_group), width %d" % dom_w,
+        roofline = {"bound": "hbm", "kernel": "aggregation (k_spmm_phased | k_spmm_wave + k_spmm_group), width %d" % dom_w,
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name, dom_w),
                     "bytes_per_launch": gather_bytes(E, n, dom_w, esize), "avg_launch_ms": avg}
