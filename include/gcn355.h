@@ -127,7 +127,8 @@ int gcn_augment_partition(int64_t n, int64_t nnz, const int64_t *rowptr, const i
 int gcn_gather_rows(const void *src, size_t row_bytes, const int32_t *idx, int64_t n_idx, void *dst, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
- * Model: L layers of widths dims[0..L] (dims[0] = f, dims[L] = n_classes), one local copy of the
+ * Model: L layers (1..16) of widths dims[0..L] (dims[0] = f <= 4096, dims[L] = n_classes; dims[1..L] at most 256
+ * with GCN_F32 and 512 with GCN_BF16, else GCN_EINVAL), one local copy of the
  * network as each worker holds it (Section 3.2).  dropout_p in [0, 1) applies to hidden activations
  * in training mode only; the keep mask is the integer function
  *     keep(e) = [ (mix(key + e * 0x9E3779B97F4A7C15) >> 32) >= floor(p * 2^32) ],

@@ -228,10 +228,14 @@ bool want_l1_cached(int32_t n_layers, const int32_t *dims) {
     return knob >= 2 || dims[0] <= dims[1];
 }
 
-int check_dims(int32_t n_layers, const int32_t *dims) {
+// Layer widths: 1..16 layers; the input may be up to 4096 wide; hidden and output widths are limited to what one
+// aggregation launch covers with a wave per row (64 lanes x 16 bytes): 256 columns in float32, 512 in bfloat16.
+int check_dims(int32_t n_layers, const int32_t *dims, int dtype) {
     if (n_layers < 1 || n_layers > 16 || !dims) return GCN_EINVAL;
-    for (int l = 0; l <= n_layers; ++l)
-        if (dims[l] < 1 || dims[l] > 256 * 4) return GCN_EINVAL;
+    if (dims[0] < 1 || dims[0] > 4096) return GCN_EINVAL;
+    const int max_w = dtype == GCN_BF16 ? 512 : 256;
+    for (int l = 1; l <= n_layers; ++l)
+        if (dims[l] < 1 || dims[l] > max_w) return GCN_EINVAL;
     return GCN_OK;
 }
 
@@ -486,7 +490,7 @@ int gcn_gather_rows(const void *src, size_t row_bytes, const int32_t *idx, int64
 
 // ------------------------------------------------------------------------------------------- model
 int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype, size_t *bytes) {
-    if (!g || !bytes || check_dims(n_layers, dims) || (dtype != GCN_F32 && dtype != GCN_BF16)) {
+    if (!g || !bytes || (dtype != GCN_F32 && dtype != GCN_BF16) || check_dims(n_layers, dims, dtype)) {
         set_error("gcn_model_workspace_bytes: bad argument");
         return GCN_EINVAL;
     }
@@ -507,8 +511,9 @@ int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_
 int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, const int32_t *dims, int dtype,
                      float dropout_p, uint64_t seed, void *workspace, size_t workspace_bytes, void *stream) {
     if (out) *out = nullptr;
-    if (!out || !g || check_dims(n_layers, dims)) {
-        set_error("gcn_model_create: null pointer or bad layer widths");
+    if (!out || !g || check_dims(n_layers, dims, dtype == GCN_BF16 ? GCN_BF16 : GCN_F32)) {
+        set_error("gcn_model_create: null pointer or bad layer widths (1..16 layers, input <= 4096 wide, other widths <= 256 "
+                  "in float32 and <= 512 in bfloat16)");
         return GCN_EINVAL;
     }
     if ((dtype != GCN_F32 && dtype != GCN_BF16) || dtype != g->store_dtype) {
