@@ -102,3 +102,77 @@ def induced_subgraph(n: int, rowptr, col, vertices):
                 out_col.append(int(new_id[u]))
         out_ptr.append(len(out_col))
     return np.array(out_ptr, dtype=np.int64), np.array(out_col, dtype=np.int32)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# The same reading with numpy arrays instead of Python sets, for graphs of full size (tens of millions of
+# edges).  Checked against the set version above on small graphs by the CPU tests.
+def _mix_np(z):
+    z = z + np.uint64(0x9E3779B97F4A7C15)
+    z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+    z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+    return z ^ (z >> np.uint64(31))
+
+
+def sample_keys_np(seed: int, v):
+    with np.errstate(over="ignore"):
+        k0 = _mix_np(np.array([seed & _M], dtype=np.uint64))[0]
+        return _mix_np(k0 ^ np.asarray(v, dtype=np.uint64))
+
+
+def _neighbours_of(rowptr, col, rows):
+    """All column entries of the given rows (with repeats)."""
+    lens = rowptr[rows + 1] - rowptr[rows]
+    if lens.sum() == 0:
+        return np.empty(0, dtype=np.int64)
+    starts = np.repeat(rowptr[rows], lens)
+    within = np.arange(lens.sum()) - np.repeat(np.cumsum(lens) - lens, lens)
+    return col[starts + within].astype(np.int64)
+
+
+def augmented_partition_np(n: int, rowptr, col, part, n_parts: int, p: int, overlap: float, seed: int):
+    """-> (vertices, n_local), as augmented_partition."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    col = np.asarray(col)
+    part = np.asarray(part)
+    local = np.nonzero(part == p)[0]
+    nts = vertices_to_sample(overlap, len(local), n_parts)
+    taken = np.zeros(n, dtype=bool)
+    for op in range(n_parts):
+        if op == p or nts == 0:
+            continue
+        need = nts
+        frontier = local
+        visited = np.zeros(n, dtype=bool)
+        while need > 0:
+            nb = _neighbours_of(rowptr, col, frontier)
+            nb = nb[(part[nb] == op) & ~visited[nb]]
+            level = np.unique(nb)
+            if level.size == 0:
+                break
+            if level.size >= need:
+                keys = sample_keys_np(seed, level)
+                taken[level[np.argsort(keys, kind="stable")[:need]]] = True
+                need = 0
+            else:
+                taken[level] = True
+                visited[level] = True
+                need -= level.size
+                frontier = level
+    return np.concatenate([local, np.nonzero(taken)[0]]).astype(np.int64), int(len(local))
+
+
+def induced_subgraph_np(n: int, rowptr, col, vertices):
+    """As induced_subgraph, vectorised."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    col = np.asarray(col)
+    new_id = -np.ones(n, dtype=np.int64)
+    new_id[vertices] = np.arange(len(vertices))
+    lens = rowptr[vertices + 1] - rowptr[vertices]
+    entries = _neighbours_of(rowptr, col, np.asarray(vertices, dtype=np.int64))
+    owner = np.repeat(np.arange(len(vertices)), lens)
+    ids = new_id[entries]
+    keep = ids >= 0
+    out_ptr = np.zeros(len(vertices) + 1, dtype=np.int64)
+    np.cumsum(np.bincount(owner[keep], minlength=len(vertices)), out=out_ptr[1:])
+    return out_ptr, ids[keep].astype(np.int32)

@@ -1,4 +1,6 @@
 """GPU subgraph approximation (Algorithm 1 + edge dropping) vs its CPU oracle: bit-exact (run with -m gpu)."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -62,6 +64,31 @@ def test_community_graph_with_partitions_of_communities(B):
     for overlap in (0.1, 0.5):
         for p in (0, 3):
             _check_against_oracle(B, wl.n, wl.rowptr, wl.col, part, 5, p, overlap, seed=11)
+
+
+def test_full_size_graph_five_partitions(B, capsys):
+    """The Reddit-shaped graph (46,600 vertices, 23.6 M stored entries) cut into 5 partitions of 10 communities;
+    partition 2 extended with the paper's 10 % overlap (2 % overhead).  Bit-exact against the array oracle."""
+    wl = workloads.reddit_partition(extra_frac=0.0)
+    n_parts, p, overlap, seed = 5, 2, 0.10, 1
+    part = (np.arange(wl.n) // (wl.n // n_parts)).clip(max=n_parts - 1).astype(np.int32)
+    d = H.to_dev(wl)
+    part_dev = torch.from_numpy(part).cuda()
+    B.gcn_augment_partition(d["rowptr"], d["col"], part_dev, n_parts, p, overlap, seed)      # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    v, n_local, rp, cl = B.gcn_augment_partition(d["rowptr"], d["col"], part_dev, n_parts, p, overlap, seed)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    want_v, want_nl = SA.augmented_partition_np(wl.n, wl.rowptr, wl.col, part, n_parts, p, overlap, seed)
+    want_rp, want_cl = SA.induced_subgraph_np(wl.n, wl.rowptr, wl.col, want_v)
+    assert n_local == want_nl == 9320 and len(want_v) - want_nl == 4 * 233          # nts = floor(0.1 * 9320 / 4)
+    np.testing.assert_array_equal(v.cpu().numpy(), want_v)
+    np.testing.assert_array_equal(rp.cpu().numpy(), want_rp)
+    np.testing.assert_array_equal(cl.cpu().numpy(), want_cl)
+    with capsys.disabled():
+        print("\n    gcn_augment_partition: %d vertices / %d entries -> %d + %d vertices, %d entries in %.1f ms"
+              % (wl.n, wl.nnz, n_local, len(want_v) - n_local, len(want_cl), dt * 1e3), end="", flush=True)
 
 
 def test_bad_arguments(B):

@@ -116,3 +116,20 @@ def test_levels_against_dense_boolean_algebra(n, p_edge, n_parts, overlap, seed)
         for i in range(len(v)):
             got[i, cl[rp[i]:rp[i + 1]]] = True
         np.testing.assert_array_equal(got, sub)
+
+
+@pytest.mark.parametrize("n,p_edge,n_parts,overlap,seed", [(120, 0.05, 3, 0.4, 7), (150, 0.015, 4, 1.5, 8),
+                                                            (100, 0.2, 5, 0.2, 9)])
+def test_array_version_equals_set_version(n, p_edge, n_parts, overlap, seed):
+    _, rowptr, col, part = _random_partitioned_graph(n, p_edge, n_parts, seed)
+    for p in range(n_parts):
+        v, nl, _ = SA.augmented_partition(n, rowptr, col, part, n_parts, p, overlap, seed)
+        v2, nl2 = SA.augmented_partition_np(n, rowptr, col, part, n_parts, p, overlap, seed)
+        assert nl == nl2
+        np.testing.assert_array_equal(v, v2)
+        rp, cl = SA.induced_subgraph(n, rowptr, col, v)
+        rp2, cl2 = SA.induced_subgraph_np(n, rowptr, col, v2)
+        np.testing.assert_array_equal(rp, rp2)
+        np.testing.assert_array_equal(cl, cl2)
+    for v in (0, 1, 77, 2 ** 31 - 1):
+        assert int(SA.sample_keys_np(seed, np.array([v]))[0]) == SA.sample_key(seed, v)
