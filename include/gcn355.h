@@ -87,6 +87,26 @@ int gcn_graph_destroy(gcn_graph *g);
 /* Sizes: n, E = nonzeros of A + I, size of the train mask, largest degree.  Any pointer may be NULL. */
 int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_train, int32_t *max_degree);
 
+/* Dense tiles.  The aggregation of Section 4.1's layer rule (the nnz(A) F term of Section 5.4's cost model)
+ * runs in two parts when the adjacency pattern has dense blocks, as the partitions of a community-structured
+ * graph do (Section 3): the pattern is cut into aligned 32 x 32 tiles; tiles with at least `tile_min_entries`
+ * stored entries (tunable, default 128, allowed 64..1024) are kept as 32 words of 32 bits and multiplied on the
+ * matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The split is used for
+ * float32 matrices when the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this
+ * rule, 0 never, 1 whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off
+ * per call).  Sums are float32 either way; only their order differs.  A non-finite value in a row of the
+ * aggregated matrix reaches, through 0 x inf, all 32 rows of the tiles that cover it.
+ * gcn_graph_tile_info: number of dense tiles, stored entries inside them, 1 if the split is in use.
+ * gcn_graph_get_tiles (only when in use; any pointer may be NULL; asynchronous on `stream` except *res_nnz):
+ *   tile_ptr [dev, ceil(n/32)+1 int64]  dense tiles of row tile i are tile_ptr[i] .. tile_ptr[i+1]
+ *   tile_col [dev, n_tiles int32]       their column tiles, ascending inside a row tile
+ *   bits     [dev, n_tiles*32 uint32]   word r of tile k: bit c set = entry (32 i + r, 32 tile_col[k] + c)
+ *   res_rowptr [dev, n+1 int64], res_col [dev, *res_nnz int32]  the residual pattern, rows sorted
+ *   res_nnz  [host] E minus the entries inside dense tiles */
+int gcn_graph_tile_info(const gcn_graph *g, int64_t *n_tiles, int64_t *nnz_dense, int32_t *in_use);
+int gcn_graph_get_tiles(const gcn_graph *g, int64_t *tile_ptr, int32_t *tile_col, uint32_t *bits,
+                        int64_t *res_rowptr, int32_t *res_col, int64_t *res_nnz, void *stream);
+
 /* Copies the canonical arrays to caller buffers [dev]: rowptr (n+1 int64), col (E int32), deg (n int32),
  * dinv (n float32).  Any pointer may be NULL.  Asynchronous on `stream`. */
 int gcn_graph_get_csr(const gcn_graph *g, int64_t *rowptr, int32_t *col, int32_t *deg, float *dinv, void *stream);

@@ -85,6 +85,11 @@ struct gcn_graph {
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;
     PrepBuffers pb{};
+    // dense tiles and the residual pattern beside them (in use only when the tiles hold enough of the entries)
+    TileBuffers tiles{};
+    PrepBuffers res{};
+    int64_t n_tiles = 0, nnz_dense = 0, res_n_heavy = 0;
+    bool use_tiles = false;
     void *x = nullptr;           // (n + 1) x ldf elements of store_dtype, zero padded, last row zero
     int32_t *labels = nullptr;
     uint8_t *mask = nullptr;
@@ -141,14 +146,23 @@ bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
                    int cols, int width, int epilogue) {
     SpmmArgs a{};
-    a.rowptr = g->pb.rowptr;
-    a.col = g->pb.col;
-    a.perm = g->pb.perm;
+    // the dense-tile form handles float32 matrices; everything else gathers over the whole pattern
+    const bool tiles = g->use_tiles && t_dtype == GCN_F32 && out_dtype == GCN_F32 && tunable("spmm_tiles", -1) != 0;
+    const PrepBuffers &pb = tiles ? g->res : g->pb;
+    a.rowptr = pb.rowptr;
+    a.col = pb.col;
+    a.perm = pb.perm;
     a.dinv = g->pb.dinv;
-    a.segoff = g->pb.segoff;
-    a.prow = g->pb.prow;
+    a.segoff = pb.segoff;
+    a.prow = pb.prow;
     a.n = g->n;
-    a.n_heavy = g->n_heavy;
+    a.n_heavy = tiles ? g->res_n_heavy : g->n_heavy;
+    if (tiles) {
+        a.tile_ptr = g->tiles.tile_ptr;
+        a.tile_col = g->tiles.tile_col;
+        a.bits = g->tiles.bits;
+        a.n_rt = g->tiles.n_rt;
+    }
     a.t = t;
     a.t_dtype = t_dtype;
     a.ld_t = ld_t;
@@ -176,9 +190,27 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.hpos = c.take<int64_t>(n + 1);
     g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     int pw = 0, pr = 0;
-    g.pb.prow = phased_shape(n, &pw, &pr) ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
+    const bool phased = phased_shape(n, &pw, &pr);   // (a null pointer says nothing here: a measuring Carver returns null)
+    g.pb.prow = phased ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
     g.pb.flags = c.take<int32_t>(16);
+    TileBuffers &tb = g.tiles;
+    tb.n_rt = (n + 31) / 32;
+    tb.capacity = (int64_t)tiles_capacity(cap);
+    tb.tile_cnt = c.take<int32_t>(tb.n_rt);
+    tb.tile_ptr = c.take<int64_t>(tb.n_rt + 1);
+    tb.tile_col = c.take<int32_t>(tb.capacity);
+    tb.tile_rt = c.take<int32_t>(tb.capacity);
+    tb.bits = c.take<uint32_t>((size_t)tb.capacity * 32);
+    tb.totals = c.take<unsigned long long>(2);
+    g.res = g.pb;   // shares dinv and the creation-time scratch arrays; its own pattern and schedule follow
+    g.res.rowptr = c.take<int64_t>(n + 1);
+    g.res.col = c.take<int32_t>(cap + kColSlack);
+    g.res.deg = c.take<int32_t>(n);
+    g.res.perm = c.take<int32_t>(n);
+    g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
+    g.res.prow = phased ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
+    g.res.flags = c.take<int32_t>(16);
     g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
     g.labels = c.take<int32_t>(n);
     g.mask = c.take<uint8_t>(n);
@@ -295,6 +327,11 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     g->store_dtype = store_dtype;
     Carver c(workspace);
     carve_graph(c, *g);   // uses store_dtype
+    if (c.bytes() != need) {   // the measuring pass and this one must lay out the same buffers
+        set_error("gcn_graph_create: internal layout mismatch (%zu bytes carved, %zu measured)", c.bytes(), need);
+        delete g;
+        return GCN_EINVAL;
+    }
     int32_t flags[16];
 
 #define FAIL_IF(expr)            \
@@ -358,6 +395,39 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     g->E = ends[0];
     g->n_heavy = flags[4];
     g->max_deg = flags[3];
+
+    // Dense tiles: select, then decide.  Knobs read here: "tile_min_entries" (default 128 of 1024), "spmm_tiles"
+    // (-1: use the tiles when they hold at least a quarter of the entries, 0: never build, 1: whenever there is one).
+    const int64_t tiles_knob = tunable("spmm_tiles", -1);
+    if (tiles_knob != 0) {
+        int64_t me = tunable("tile_min_entries", 128);
+        if (me < kTileMinEntriesFloor) me = kTileMinEntriesFloor;
+        if (me > 1024) me = 1024;
+        FAIL_IF(tiles_select(n, g->pb.rowptr, g->pb.col, (int)me, g->tiles, g->pb.blocksum, st));
+        unsigned long long dense = 0;
+        HIP_OR_FAIL(hipMemcpyAsync(&g->n_tiles, g->tiles.tile_ptr + g->tiles.n_rt, sizeof(int64_t),
+                                   hipMemcpyDeviceToHost, st));
+        HIP_OR_FAIL(hipMemcpyAsync(&dense, g->tiles.totals, sizeof(dense), hipMemcpyDeviceToHost, st));
+        HIP_OR_FAIL(hipStreamSynchronize(st));
+        g->nnz_dense = (int64_t)dense;
+        if (g->n_tiles > g->tiles.capacity) {   // cannot happen: every tile holds >= kTileMinEntriesFloor entries
+            set_error("gcn_graph_create: dense tile count %lld exceeds capacity", (long long)g->n_tiles);
+            delete g;
+            return GCN_EINVAL;
+        }
+        g->use_tiles = g->n_tiles > 0 && (tiles_knob > 0 || g->nnz_dense * 4 >= g->E);
+        if (g->use_tiles) {
+            FAIL_IF(tiles_build(n, g->pb.rowptr, g->pb.col, g->n_tiles, g->tiles, g->res, st));
+            FAIL_IF(fill_zero(g->res.flags, 16 * sizeof(int32_t), st));
+            FAIL_IF(prep_schedule(n, g->res, st));
+            int pw = 0, pr = 0;
+            if (g->res.prow && phased_shape(n, &pw, &pr))
+                FAIL_IF(prep_balance_rows(n, g->res.deg, pw, pr, g->res.prow, st));
+            HIP_OR_FAIL(hipMemcpyAsync(flags, g->res.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+            HIP_OR_FAIL(hipStreamSynchronize(st));
+            g->res_n_heavy = flags[4];
+        }
+    }
 #undef FAIL_IF
 #undef HIP_OR_FAIL
     *out = g;
@@ -378,6 +448,44 @@ int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_trai
     if (nnz) *nnz = g->E;
     if (n_train) *n_train = g->n_train;
     if (max_degree) *max_degree = g->max_deg;
+    return GCN_OK;
+}
+
+int gcn_graph_tile_info(const gcn_graph *g, int64_t *n_tiles, int64_t *nnz_dense, int32_t *in_use) {
+    if (!g) {
+        set_error("gcn_graph_tile_info: null graph");
+        return GCN_EINVAL;
+    }
+    if (n_tiles) *n_tiles = g->n_tiles;
+    if (nnz_dense) *nnz_dense = g->nnz_dense;
+    if (in_use) *in_use = g->use_tiles ? 1 : 0;
+    return GCN_OK;
+}
+
+int gcn_graph_get_tiles(const gcn_graph *g, int64_t *tile_ptr, int32_t *tile_col, uint32_t *bits,
+                        int64_t *res_rowptr, int32_t *res_col, int64_t *res_nnz, void *stream) {
+    if (!g) {
+        set_error("gcn_graph_get_tiles: null graph");
+        return GCN_EINVAL;
+    }
+    if (!g->use_tiles) {
+        set_error("gcn_graph_get_tiles: this graph does not use dense tiles");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t res_E = g->E - g->nnz_dense;
+    if (res_nnz) *res_nnz = res_E;
+    if (tile_ptr)
+        GCN_HIP(hipMemcpyAsync(tile_ptr, g->tiles.tile_ptr, (g->tiles.n_rt + 1) * sizeof(int64_t),
+                               hipMemcpyDeviceToDevice, st));
+    if (tile_col)
+        GCN_HIP(hipMemcpyAsync(tile_col, g->tiles.tile_col, g->n_tiles * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    if (bits)
+        GCN_HIP(hipMemcpyAsync(bits, g->tiles.bits, g->n_tiles * 32 * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    if (res_rowptr)
+        GCN_HIP(hipMemcpyAsync(res_rowptr, g->res.rowptr, (g->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+    if (res_col && res_E > 0)
+        GCN_HIP(hipMemcpyAsync(res_col, g->res.col, res_E * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     return GCN_OK;
 }
 
@@ -551,6 +659,11 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
                                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
     Carver c(workspace);
     carve_model(c, *m);
+    if (c.bytes() != need) {   // the measuring pass and this one must lay out the same buffers
+        set_error("gcn_model_create: internal layout mismatch (%zu bytes carved, %zu measured)", c.bytes(), need);
+        delete m;
+        return GCN_EINVAL;
+    }
     // zero everything once: padding columns, the extra zero rows and the weights start at zero
     hipStream_t st = (hipStream_t)stream;
     rc = fill_zero(workspace, need, st);

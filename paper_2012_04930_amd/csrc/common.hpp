@@ -42,6 +42,7 @@ constexpr int kColSlack = 64;  // readable entries after the last column index (
 constexpr int kHeavyDegree = 32;  // rows with at least this many entries get a whole wave in the aggregation
 constexpr int kColBlocks = 8;     // column ranges of the phased aggregation schedule, one per XCD
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
+constexpr int kTileMinEntriesFloor = 64;   // a dense 32 x 32 tile holds at least this many entries (bounds their number)
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int padded_width(int w) { return (int)round_up(w, kLdAlign); }
@@ -101,6 +102,26 @@ inline bool phased_shape(int64_t n, int *W, int *R) {
     return true;
 }
 int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st);
+// ---------------------------------------------------------------------------------------------
+// Dense 32 x 32 tiles of the adjacency pattern (tiles.hip)
+struct TileBuffers {
+    int64_t n_rt = 0;       // row tiles = column tiles = ceil(n / 32)
+    int64_t capacity = 0;   // dense tiles the arrays can hold
+    int32_t *tile_cnt = nullptr;   // n_rt: dense tiles of each row tile
+    int64_t *tile_ptr = nullptr;   // n_rt + 1: exclusive prefix of tile_cnt
+    int32_t *tile_col = nullptr;   // capacity: column tile of each dense tile, ascending inside a row tile
+    int32_t *tile_rt = nullptr;    // capacity: row tile of each dense tile
+    uint32_t *bits = nullptr;      // capacity * 32: word r of tile k = columns that row r of the tile holds
+    unsigned long long *totals = nullptr;   // [0] stored entries inside the dense tiles
+};
+size_t tiles_capacity(int64_t entries);
+// fills tile_cnt, tile_ptr, tile_col, tile_rt and totals from the canonical pattern
+int tiles_select(int64_t n, const int64_t *rowptr, const int32_t *col, int min_entries, TileBuffers &tb,
+                 int64_t *blocksum, hipStream_t st);
+// fills bits, and res.deg / res.rowptr / res.col with the entries outside the dense tiles
+int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_tiles, TileBuffers &tb,
+                PrepBuffers &res, hipStream_t st);
+
 int prep_labels_mask(int64_t n, const int32_t *labels, const uint8_t *mask, int32_t n_classes, int32_t *labels_out,
                      uint8_t *mask_out, int32_t *flags, hipStream_t st);
 size_t scan_blocks(int64_t n);
@@ -170,7 +191,16 @@ struct SpmmArgs {
     uint32_t drop_threshold;
     float keep_scale;
     uint64_t drop_key;
+    // Dense tiles (tile_ptr null: none).  With tiles, rowptr / col / perm / segoff / prow describe the residual
+    // pattern, and the launch first writes the tiles' sums to out, then adds the residual rows and finishes.
+    const int64_t *tile_ptr;
+    const int32_t *tile_col;
+    const uint32_t *bits;
+    int64_t n_rt;
+    bool accumulate;     // set by spmm_launch: out already holds the tiles' sums, to be added before a row is finished
 };
+// out = the sums over the dense tiles only (float32, no scaling)
+int tiles_launch(const SpmmArgs &a, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------

@@ -31,13 +31,32 @@ typedef Activation Epi;
 __device__ inline float finish(float v, const Epi &ep, int64_t row, int c) { return activate(v, ep, row, c); }
 
 // The lane's piece of output row r (columns sub * V ...), scaled by d = d_r^-1/2 and finished.
+// The sums that the dense-tile launch left in the output (float32 outputs only; never asked for with bfloat16).
+template <int V>
+__device__ inline void add_stored(const float *p, float (&o)[V]) {
+#pragma unroll
+    for (int i = 0; i < V; i += 4) {
+        const float4 q = *reinterpret_cast<const float4 *>(p + i);
+        o[i] += q.x;
+        o[i + 1] += q.y;
+        o[i + 2] += q.z;
+        o[i + 3] += q.w;
+    }
+}
+template <int V>
+__device__ inline void add_stored(const bf16_t *, float (&)[V]) {}
+
+// accumulate: the output already holds the sums over the row's dense tiles; they are added first.
 template <typename TOut, int V>
 __device__ inline void store_row_piece(TOut *__restrict__ out, int ld_out, int r, int sub, const float (&a)[V], float d,
-                                       const Epi &ep) {
+                                       const Epi &ep, bool accumulate) {
     const int c0 = sub * V;
     float o[V];
 #pragma unroll
-    for (int i = 0; i < V; ++i) o[i] = finish(a[i] * d, ep, r, c0 + i);
+    for (int i = 0; i < V; ++i) o[i] = a[i];
+    if (accumulate) add_stored<V>(out + (int64_t)r * ld_out + c0, o);
+#pragma unroll
+    for (int i = 0; i < V; ++i) o[i] = finish(o[i] * d, ep, r, c0 + i);
     store_elems<V>(out + (int64_t)r * ld_out + c0, o);
 }
 
@@ -134,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
                                                         const float *__restrict__ dinv, int zero_row,
                                                         int64_t n_rows, const TIn *__restrict__ t, int ld_t,
                                                         TOut *__restrict__ out, int ld_out, int cols, int nblocks,
-                                                        Epi ep) {
+                                                        Epi ep, bool accumulate) {
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
     constexpr int STEP = GPW * U;      // neighbours per unrolled step
@@ -164,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
 #pragma unroll
         for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
     }
-    if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
+    if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep, accumulate);
 }
 
 // ------------------------------------------------------------------------------------------------ phased schedule
@@ -185,7 +204,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
                                                           const int32_t *__restrict__ prow, int W,
                                                           const float *__restrict__ dinv, int zero_row, int64_t n,
                                                           int64_t block, const TIn *__restrict__ t, int ld_t,
-                                                          TOut *__restrict__ out, int ld_out, int cols, Epi ep) {
+                                                          TOut *__restrict__ out, int ld_out, int cols, Epi ep,
+                                                          bool accumulate) {
     constexpr int V = Piece<TIn>::kElems;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -234,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
 #pragma unroll
                 for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
             }
-            if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, (int)r, sub, a, dinv[r], ep);
+            if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, (int)r, sub, a, dinv[r], ep, accumulate);
         }
     }
 }
@@ -247,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
                                                          const float *__restrict__ dinv, int zero_row,
                                                          int64_t n_rows, const TIn *__restrict__ t, int ld_t,
                                                          TOut *__restrict__ out, int ld_out, int cols, int nblocks,
-                                                         Epi ep) {
+                                                         Epi ep, bool accumulate) {
     static_assert(LPR % U == 0, "one index fetch feeds a whole number of unrolled steps");
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;                 // rows per wave
@@ -294,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
         float a[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) a[i] = acc0[i] + acc1[i];
-        store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep);
+        store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep, accumulate);
     }
 }
 
@@ -316,10 +336,10 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
             k_spmm_wave<TIn, TOut, LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.accumulate);
         else
             k_spmm_wave<TIn, TOut, LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.accumulate);
         GCN_LAUNCH_CHECK();
     }
     const int64_t n_light = a.n - a.n_heavy;
@@ -330,17 +350,17 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         if (narrow)
             k_spmm_group<TIn, TOut, LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
                 a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
-                ep);
+                ep, a.accumulate);
         else
             k_spmm_group<TIn, TOut, LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
                 a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
-                ep);
+                ep, a.accumulate);
         GCN_LAUNCH_CHECK();
     }
     return GCN_OK;
 }
 
-// The phased schedule applies when every row is heavy, the input is larger than one L2 but one column range of it
+// The phased schedule applies when nearly every row is heavy, the input is larger than one L2 but one column range of it
 // (an eighth) fits, and a wave gets at most 8 rows with the whole grid resident.  Knob "spmm_phased": -1 automatic
 // (default), 0 never, 1 whenever the shape allows.
 constexpr int64_t kL2Bytes = 4 << 20;
@@ -349,9 +369,8 @@ template <typename TIn, typename TOut, int LPR, int U>
 bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     const int64_t knob = tunable("spmm_phased", -1);
     int W = 0, R = 0;
-    if (knob == 0 || !a.segoff || !a.prow || a.n_heavy != a.n || !narrow_ok(a, sizeof(TIn)) ||
-        !phased_shape(a.n, &W, &R))
-        return false;
+    if (knob == 0 || !a.segoff || !a.prow || !narrow_ok(a, sizeof(TIn)) || !phased_shape(a.n, &W, &R)) return false;
+    if (knob < 0 && a.n_heavy * 8 < a.n * 7) return false;   // a wave per light row wastes most of its lanes
     const int64_t block = (a.n + kColBlocks - 1) / kColBlocks;
     const int64_t row_bytes = (int64_t)a.ld_t * (int64_t)sizeof(TIn);
     if (knob < 0 && ((a.n + 1) * row_bytes <= kL2Bytes || block * row_bytes > kL2Bytes - (512 << 10))) return false;
@@ -363,7 +382,7 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
 #define GCN_PHASED(RR)                                                                                               \
     k_spmm_phased<TIn, TOut, LPR, U, RR><<<dim3(grid), dim3(kThreads), 0, st>>>(                                      \
         a.rowptr, a.col, a.segoff, a.prow, W, a.dinv, zero_row, a.n, block, t, a.ld_t, out, a.ld_out, \
-        a.cols, ep)
+        a.cols, ep, a.accumulate)
     if (R == 4) GCN_PHASED(4);
     else if (R == 6) GCN_PHASED(6);
     else GCN_PHASED(8);
@@ -411,10 +430,18 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         return GCN_EINVAL;
     }
     timing_begin(a.width, st);
-    int rc;
-    if (a.t_dtype == GCN_F32) rc = launch_by_width<float, float>(a, st);
-    else if (a.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(a, st);
-    else rc = launch_by_width<bf16_t, bf16_t>(a, st);
+    SpmmArgs b = a;
+    b.accumulate = false;
+    int rc = GCN_OK;
+    if (a.tile_ptr) {
+        rc = tiles_launch(a, st);
+        b.accumulate = true;
+    }
+    if (rc == GCN_OK) {
+        if (a.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, st);
+        else if (a.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, st);
+        else rc = launch_by_width<bf16_t, bf16_t>(b, st);
+    }
     timing_end(st);
     return rc;
 }

@@ -1,0 +1,165 @@
+"""Dense 32 x 32 tiles of the adjacency pattern: the split of the pattern is integer work and is compared bit by
+bit with a numpy restatement of its definition; the aggregation that uses it is compared with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from synth import graphs, rng, workloads
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2012_04930_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture()
+def knobs(B):
+    """Sets tunables for one test and puts the defaults back afterwards."""
+    touched = []
+
+    def set_(name, value):
+        touched.append(name)
+        B.gcn_set_tunable(name, value)
+    yield set_
+    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1}
+    for name in touched:
+        B.gcn_set_tunable(name, defaults[name])
+
+
+def tile_split(n, rowptr, col, min_entries):
+    """The definition: count the stored entries of every aligned 32 x 32 tile of the canonical pattern; tiles with at
+    least min_entries are dense.  -> tile_ptr, tile_col, bits [n_tiles x 32] (uint32), res_rowptr, res_col"""
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    n_rt = (n + 31) // 32
+    key = (rows // 32) * n_rt + col // 32
+    uniq, inverse, cnt = np.unique(key, return_inverse=True, return_counts=True)
+    dense = cnt >= min_entries
+    dkeys = uniq[dense]                                     # ascending: by row tile, then column tile
+    tile_ptr = np.zeros(n_rt + 1, dtype=np.int64)
+    np.cumsum(np.bincount(dkeys // n_rt, minlength=n_rt), out=tile_ptr[1:])
+    tile_col = (dkeys % n_rt).astype(np.int32)
+    in_dense = dense[inverse]
+    tile_of_entry = np.cumsum(dense)[inverse] - 1            # index among the dense tiles
+    bits = np.zeros((len(dkeys), 32), dtype=np.uint32)
+    np.bitwise_or.at(bits, (tile_of_entry[in_dense], rows[in_dense] % 32),
+                     (np.uint32(1) << (col[in_dense] % 32).astype(np.uint32)))
+    res_rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows[~in_dense], minlength=n), out=res_rowptr[1:])
+    return tile_ptr, tile_col, bits, res_rowptr, col[~in_dense].astype(np.int32), int(in_dense.sum())
+
+
+def _complete_blocks(n, block):
+    """Disjoint cliques of `block` vertices (the last one smaller): every tile inside a clique is full."""
+    u, v = [], []
+    for b0 in range(0, n, block):
+        m = min(block, n - b0)
+        a, b = np.triu_indices(m, 1)
+        u.append(a + b0)
+        v.append(b + b0)
+    return graphs.pairs_to_csr(n, np.concatenate(u), np.concatenate(v))
+
+
+def _cases():
+    yield "partition_2.4k", workloads.reddit_partition(scale=0.05), 64
+    yield "partition_4.7k_thr128", workloads.reddit_partition(scale=0.1), 128
+    wl = workloads.tiny(n=331)                 # 331 = 10 * 32 + 11: ragged last tile, cliques of 96 and a last of 43
+    wl.rowptr, wl.col = _complete_blocks(331, 96)
+    yield "cliques_331", wl, 64
+
+
+@pytest.mark.parametrize("case", list(_cases()), ids=lambda c: c[0])
+def test_tile_split_is_bit_exact(B, oracle, knobs, case):
+    _, wl, thr = case
+    knobs("spmm_tiles", 1)
+    knobs("tile_min_entries", thr)
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    want = tile_split(wl.n, og.rowptr, og.col, thr)
+    info = B.gcn_graph_tile_info(g)
+    assert info["in_use"] and info["n_tiles"] == len(want[1]) and info["nnz_dense"] == want[5] > 0
+    got = [t.cpu().numpy() for t in B.gcn_graph_get_tiles(g)]
+    np.testing.assert_array_equal(got[0], want[0])
+    np.testing.assert_array_equal(got[1], want[1])
+    np.testing.assert_array_equal(got[2].view(np.uint32), want[2])
+    np.testing.assert_array_equal(got[3], want[3])
+    np.testing.assert_array_equal(got[4], want[4])
+    # the canonical pattern itself is reported unchanged
+    rowptr, col, _, _ = B.gcn_graph_get_csr(g)
+    np.testing.assert_array_equal(rowptr.cpu().numpy(), og.rowptr)
+    np.testing.assert_array_equal(col.cpu().numpy(), og.col)
+
+
+def test_all_entries_dense_leaves_an_empty_residual(B, oracle, knobs):
+    wl = workloads.tiny(n=256)
+    wl.rowptr, wl.col = _complete_blocks(256, 64)        # 4 cliques of 64: 16 full tiles, nothing else
+    knobs("spmm_tiles", 1)
+    knobs("tile_min_entries", 1024)
+    g = H.gpu_graph(B, wl)
+    info = B.gcn_graph_tile_info(g)
+    assert info == {"n_tiles": 16, "nnz_dense": 256 * 64, "in_use": True}
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    x = rng.normal_f32(5, 1, wl.n * 40).reshape(wl.n, 40)
+    got = B.gcn_aggregate(g, torch.from_numpy(x).cuda()).cpu().numpy()
+    H.assert_close(got, oracle.aggregate(og, x), what="all dense")
+    # closed form: A_hat of disjoint 64-cliques averages each clique
+    want = x.reshape(4, 64, 40).astype(np.float64).mean(axis=1, keepdims=True).repeat(64, 1).reshape(256, 40)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-6)
+
+
+@pytest.mark.parametrize("width", [1, 8, 31, 41, 64, 100, 128, 130, 256])
+@pytest.mark.parametrize("case", list(_cases()), ids=lambda c: c[0])
+def test_aggregate_with_tiles_matches_oracle(B, oracle, knobs, case, width):
+    _, wl, thr = case
+    knobs("spmm_tiles", 1)
+    knobs("tile_min_entries", thr)
+    g = H.gpu_graph(B, wl)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    x = rng.normal_f32(width, 4, wl.n * width).reshape(wl.n, width)
+    xd = torch.from_numpy(x).cuda()
+    got = B.gcn_aggregate(g, xd).cpu().numpy()
+    ref = oracle.aggregate(og, x)
+    H.assert_close(got, ref, what="tiles + residual, width %d" % width)
+    # the same graph gathered whole: same terms in another order
+    knobs("spmm_tiles", 0)
+    plain = B.gcn_aggregate(g, xd).cpu().numpy()
+    knobs("spmm_tiles", 1)
+    H.assert_close(plain, ref, what="gather only, width %d" % width)
+    np.testing.assert_allclose(got, plain, rtol=0, atol=4e-6 * np.abs(ref).max())
+    # bfloat16 storage does not take the tile form and must still be right on such a graph
+    if width in (41, 128):
+        got16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
+        H.assert_close(got16, ref, rtol=H.RTOL_BF16, what="bf16 on a tiled graph")
+
+
+def test_automatic_choice(B, knobs):
+    """Default rule: tiles in use when they hold at least a quarter of the entries."""
+    dense = H.gpu_graph(B, workloads.reddit_partition(scale=0.1))
+    sparse = H.gpu_graph(B, workloads.chung_lu_mid(scale=0.05))
+    assert B.gcn_graph_tile_info(dense)["in_use"]
+    info = B.gcn_graph_tile_info(sparse)
+    assert not info["in_use"] and info["nnz_dense"] * 4 < B.gcn_graph_info(sparse)["nnz"]
+    with pytest.raises(B.GcnError):
+        B.gcn_graph_get_tiles(sparse)
+    knobs("spmm_tiles", 0)
+    off = H.gpu_graph(B, workloads.reddit_partition(scale=0.1))
+    assert B.gcn_graph_tile_info(off) == {"n_tiles": 0, "nnz_dense": 0, "in_use": False}
+
+
+@pytest.mark.parametrize("dropout_p", [0.0, 0.5])
+def test_full_step_with_tiles(B, oracle, knobs, dropout_p):
+    wl = workloads.reddit_partition(scale=0.08)
+    knobs("spmm_tiles", 1)
+    knobs("tile_min_entries", 64)
+    g = H.gpu_graph(B, wl)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+    for cache_ax in (0, 2):
+        _, gpu = H.gpu_epoch(B, g, wl, dropout_p=dropout_p, seed=5, cache_ax=cache_ax)
+        _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=dropout_p, seed=5)
+        H.compare_epoch(oracle, wl, gpu, tr, new)
