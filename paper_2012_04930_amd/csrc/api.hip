@@ -90,6 +90,14 @@ struct gcn_graph {
     PrepBuffers res{};
     int64_t n_tiles = 0, nnz_dense = 0, res_n_heavy = 0;
     bool use_tiles = false;
+    // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    ~gcn_graph() {
+        if (ev_fork) (void)hipEventDestroy(ev_fork);
+        if (ev_join) (void)hipEventDestroy(ev_join);
+        if (side) (void)hipStreamDestroy(side);
+    }
     void *x = nullptr;           // (n + 1) x ldf elements of store_dtype, zero padded, last row zero
     int32_t *labels = nullptr;
     uint8_t *mask = nullptr;
@@ -120,6 +128,7 @@ struct gcn_model {
     int64_t adam_steps = 0;
     float *partials = nullptr;
     size_t partial_floats = 0;
+    float *tile_sums = nullptr;     // n x widest aggregated matrix: the tile product's output when it runs beside the gather
     double *loss_part = nullptr;
     long long *corr_part = nullptr;
     float *result = nullptr;        // [0] loss [1] accuracy
@@ -143,8 +152,9 @@ uint64_t host_mix64(uint64_t z) {
 
 bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
+// tile_sums: n x cols floats for the tile product when it runs beside the gather kernel (null: one after the other)
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
-                   int cols, int width, int epilogue) {
+                   int cols, int width, int epilogue, float *tile_sums) {
     SpmmArgs a{};
     // the dense-tile form handles float32 matrices; everything else gathers over the whole pattern
     const bool tiles = g->use_tiles && t_dtype == GCN_F32 && out_dtype == GCN_F32 && tunable("spmm_tiles", -1) != 0;
@@ -162,6 +172,12 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
         a.tile_col = g->tiles.tile_col;
         a.bits = g->tiles.bits;
         a.n_rt = g->tiles.n_rt;
+        if (tile_sums && g->side) {
+            a.tile_sums = tile_sums;
+            a.side = g->side;
+            a.ev_fork = g->ev_fork;
+            a.ev_join = g->ev_join;
+        }
     }
     a.t = t;
     a.t_dtype = t_dtype;
@@ -243,6 +259,16 @@ void carve_model(Carver &c, gcn_model &m) {
         const size_t es = m.dtype == GCN_BF16 ? 2 : 4;
         m.pax = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
         m.xs = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
+    }
+    m.tile_sums = nullptr;
+    if (m.g->use_tiles && m.dtype == GCN_F32) {
+        int widest = 0;
+        for (auto &ly : m.layers) widest = ly.ld_out > widest ? ly.ld_out : widest;
+        if (m.l1_cached) {   // P = A_hat X is built in slabs of 256 columns
+            const int slab = 256 < m.g->ldf ? 256 : m.g->ldf;
+            widest = slab > widest ? slab : widest;
+        }
+        m.tile_sums = c.take<float>((size_t)n * widest);
     }
     m.partial_floats = pf;
     m.partials = c.take<float>(pf);
@@ -426,6 +452,9 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
             HIP_OR_FAIL(hipMemcpyAsync(flags, g->res.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
             HIP_OR_FAIL(hipStreamSynchronize(st));
             g->res_n_heavy = flags[4];
+            HIP_OR_FAIL(hipStreamCreateWithFlags(&g->side, hipStreamNonBlocking));   // default priority
+            HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_fork, hipEventDisableTiming));
+            HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_join, hipEventDisableTiming));
         }
     }
 #undef FAIL_IF
@@ -512,6 +541,7 @@ int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, 
     const int ld = padded_width(width);
     c.take<float>((size_t)(g->n + 1) * ld);
     c.take<float>((size_t)(g->n + 1) * ld);
+    c.take<float>((size_t)g->n * ld);
     *bytes = c.bytes();
     return GCN_OK;
 }
@@ -534,12 +564,13 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     const int ld = padded_width(width);
     float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
     float *z = c.take<float>((size_t)(g->n + 1) * ld);
+    float *tile_sums = c.take<float>((size_t)g->n * ld);
     const size_t es = dtype == GCN_BF16 ? 2 : 4;
     rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);
     if (rc) return rc;
     rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
     if (rc) return rc;
-    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone);
+    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone, tile_sums);
     rc = spmm_launch(a, st);
     if (rc) return rc;
     return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
@@ -675,7 +706,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
         for (int c0 = 0; !rc && c0 < g->ldf; c0 += slab) {
             const int cols = g->ldf - c0 < slab ? g->ldf - c0 : slab;
             SpmmArgs a = spmm_args(g, (const char *)m->xs + c0 * es, dtype, g->ldf, (char *)m->pax + c0 * es, dtype,
-                                   g->ldf, cols, g->f, kEpiNone);
+                                   g->ldf, cols, g->f, kEpiNone, m->tile_sums);
             rc = spmm_launch(a, st);
         }
     }
@@ -810,7 +841,7 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
         SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
-                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone);
+                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums);
         a.drop_threshold = act.drop_threshold;
         a.keep_scale = act.keep_scale;
         a.drop_key = act.drop_key;
@@ -889,7 +920,8 @@ int gcn_backward(gcn_model *m, void *stream) {
             continue;
         }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
-        SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone);
+        SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone,
+                               m->tile_sums);
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G

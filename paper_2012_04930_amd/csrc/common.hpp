@@ -197,10 +197,23 @@ struct SpmmArgs {
     const int32_t *tile_col;
     const uint32_t *bits;
     int64_t n_rt;
-    bool accumulate;     // set by spmm_launch: out already holds the tiles' sums, to be added before a row is finished
+    // Overlap of the two parts (all four set, or none): the tile product runs on `side` into tile_sums [n x cols
+    // floats] while the gather kernel writes plain sums to out on the caller's stream; a third launch adds the two
+    // and finishes the rows.  Without them the gather kernel follows the tile product and finishes the rows itself.
+    float *tile_sums;
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_join;
+    int finish_mode;     // set by spmm_launch, see SpmmFinish
 };
-// out = the sums over the dense tiles only (float32, no scaling)
-int tiles_launch(const SpmmArgs &a, hipStream_t st);
+// what the gather kernels do with a row's sum
+enum SpmmFinish {
+    kFinishRow = 0,      // scale by d_i^-1/2, activation, store
+    kFinishAddStored = 1,  // first add what the output already holds (the tiles' sums), then as above
+    kFinishPlainSum = 2    // store the plain sum (float32 output); a later launch finishes the rows
+};
+// dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling); beside_gather: the launch shares the
+// chip with the gather kernel
+int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, bool beside_gather, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------

@@ -46,17 +46,20 @@ __device__ inline void add_stored(const float *p, float (&o)[V]) {
 template <int V>
 __device__ inline void add_stored(const bf16_t *, float (&)[V]) {}
 
-// accumulate: the output already holds the sums over the row's dense tiles; they are added first.
+// mode: a SpmmFinish value
 template <typename TOut, int V>
-__device__ inline void store_row_piece(TOut *__restrict__ out, int ld_out, int r, int sub, const float (&a)[V], float d,
-                                       const Epi &ep, bool accumulate) {
+__device__ inline void store_row_piece(TOut *__restrict__ out, int ld_out, int r, int sub, const float (&a)[V],
+                                       const float *__restrict__ dinv, const Epi &ep, int mode) {
     const int c0 = sub * V;
     float o[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) o[i] = a[i];
-    if (accumulate) add_stored<V>(out + (int64_t)r * ld_out + c0, o);
+    if (mode == kFinishAddStored) add_stored<V>(out + (int64_t)r * ld_out + c0, o);
+    if (mode != kFinishPlainSum) {
+        const float d = dinv[r];
 #pragma unroll
-    for (int i = 0; i < V; ++i) o[i] = finish(o[i] * d, ep, r, c0 + i);
+        for (int i = 0; i < V; ++i) o[i] = finish(o[i] * d, ep, r, c0 + i);
+    }
     store_elems<V>(out + (int64_t)r * ld_out + c0, o);
 }
 
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
                                                         const float *__restrict__ dinv, int zero_row,
                                                         int64_t n_rows, const TIn *__restrict__ t, int ld_t,
                                                         TOut *__restrict__ out, int ld_out, int cols, int nblocks,
-                                                        Epi ep, bool accumulate) {
+                                                        Epi ep, int mode) {
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
     constexpr int STEP = GPW * U;      // neighbours per unrolled step
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
 #pragma unroll
         for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
     }
-    if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep, accumulate);
+    if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv, ep, mode);
 }
 
 // ------------------------------------------------------------------------------------------------ phased schedule
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
                                                           const float *__restrict__ dinv, int zero_row, int64_t n,
                                                           int64_t block, const TIn *__restrict__ t, int ld_t,
                                                           TOut *__restrict__ out, int ld_out, int cols, Epi ep,
-                                                          bool accumulate) {
+                                                          int mode) {
     constexpr int V = Piece<TIn>::kElems;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
 #pragma unroll
                 for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
             }
-            if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, (int)r, sub, a, dinv[r], ep, accumulate);
+            if (grp == 0 && sub * V < cols) store_row_piece<TOut, V>(out, ld_out, (int)r, sub, a, dinv, ep, mode);
         }
     }
 }
@@ -267,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
                                                          const float *__restrict__ dinv, int zero_row,
                                                          int64_t n_rows, const TIn *__restrict__ t, int ld_t,
                                                          TOut *__restrict__ out, int ld_out, int cols, int nblocks,
-                                                         Epi ep, bool accumulate) {
+                                                         Epi ep, int mode) {
     static_assert(LPR % U == 0, "one index fetch feeds a whole number of unrolled steps");
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;                 // rows per wave
@@ -314,8 +317,31 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
         float a[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) a[i] = acc0[i] + acc1[i];
-        store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv[r], ep, accumulate);
+        store_row_piece<TOut, V>(out, ld_out, r, sub, a, dinv, ep, mode);
     }
+}
+
+// ------------------------------------------------------------------------------------------------ joining the parts
+// out[r, c .. c + 4) = finish(d_r^-1/2 (out[r, c ..] + tile_sums[r, c ..])): the gather kernel's plain sums over
+// the residual entries plus the tile product's sums, one thread per four columns.
+__global__ __launch_bounds__(kThreads) void k_join_parts(float *__restrict__ out, int ld_out,
+                                                         const float *__restrict__ tile_sums, int ld_tile,
+                                                         const float *__restrict__ dinv, int64_t n, int cols, Epi ep) {
+    const int quads = cols / 4;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n * quads) return;
+    const int64_t r = i / quads;
+    const int c0 = (int)(i % quads) * 4;
+    float *o = out + r * ld_out + c0;
+    const float4 a = *reinterpret_cast<const float4 *>(o);
+    const float4 b = *reinterpret_cast<const float4 *>(tile_sums + r * ld_tile + c0);
+    const float d = dinv[r];
+    float4 v;
+    v.x = finish((a.x + b.x) * d, ep, r, c0);
+    v.y = finish((a.y + b.y) * d, ep, r, c0 + 1);
+    v.z = finish((a.z + b.z) * d, ep, r, c0 + 2);
+    v.w = finish((a.w + b.w) * d, ep, r, c0 + 3);
+    *reinterpret_cast<float4 *>(o) = v;
 }
 
 // true when every byte of the input (n + 1 rows) is addressable with a 32-bit offset
@@ -336,10 +362,10 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
         if (narrow)
             k_spmm_wave<TIn, TOut, LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.accumulate);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.finish_mode);
         else
             k_spmm_wave<TIn, TOut, LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.accumulate);
+                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.finish_mode);
         GCN_LAUNCH_CHECK();
     }
     const int64_t n_light = a.n - a.n_heavy;
@@ -350,11 +376,11 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         if (narrow)
             k_spmm_group<TIn, TOut, LPR, UG, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
                 a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
-                ep, a.accumulate);
+                ep, a.finish_mode);
         else
             k_spmm_group<TIn, TOut, LPR, UG, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
                 a.rowptr, a.col, a.perm + a.n_heavy, a.dinv, zero_row, n_light, t, a.ld_t, out, a.ld_out, a.cols, nblocks,
-                ep, a.accumulate);
+                ep, a.finish_mode);
         GCN_LAUNCH_CHECK();
     }
     return GCN_OK;
@@ -382,7 +408,7 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
 #define GCN_PHASED(RR)                                                                                               \
     k_spmm_phased<TIn, TOut, LPR, U, RR><<<dim3(grid), dim3(kThreads), 0, st>>>(                                      \
         a.rowptr, a.col, a.segoff, a.prow, W, a.dinv, zero_row, a.n, block, t, a.ld_t, out, a.ld_out, \
-        a.cols, ep, a.accumulate)
+        a.cols, ep, a.finish_mode)
     if (R == 4) GCN_PHASED(4);
     else if (R == 6) GCN_PHASED(6);
     else GCN_PHASED(8);
@@ -395,6 +421,12 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
         *rc = GCN_OK;
     }
     return true;
+}
+
+inline int hip_status(hipError_t e, const char *what) {
+    if (e == hipSuccess) return GCN_OK;
+    set_error("%s failed: %s", what, hipGetErrorString(e));
+    return GCN_EHIP;
 }
 
 template <typename TIn, typename TOut>
@@ -431,16 +463,36 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     }
     timing_begin(a.width, st);
     SpmmArgs b = a;
-    b.accumulate = false;
+    b.finish_mode = kFinishRow;
     int rc = GCN_OK;
-    if (a.tile_ptr) {
-        rc = tiles_launch(a, st);
-        b.accumulate = true;
+    const bool overlap = a.tile_ptr && a.tile_sums && a.side && a.ev_fork && a.ev_join && tunable("spmm_overlap", 1) != 0;
+    if (a.tile_ptr && overlap) {
+        // fork: the tile product on the side stream, the gather over the residual entries on the caller's
+        rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
+        if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");
+        if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, true, a.side);
+        if (rc == GCN_OK) rc = hip_status(hipEventRecord(a.ev_join, a.side), "hipEventRecord");
+        b.finish_mode = kFinishPlainSum;
+    } else if (a.tile_ptr) {
+        rc = tiles_launch(a, static_cast<float *>(a.out), a.ld_out, false, st);
+        b.finish_mode = kFinishAddStored;
     }
     if (rc == GCN_OK) {
         if (a.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, st);
         else if (a.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, st);
         else rc = launch_by_width<bf16_t, bf16_t>(b, st);
+    }
+    if (a.tile_ptr && overlap) {
+        // join, also after an error above: the caller's stream must not run ahead of work already on the side stream
+        const int rc2 = hip_status(hipStreamWaitEvent(st, a.ev_join, 0), "hipStreamWaitEvent");
+        if (rc == GCN_OK) rc = rc2;
+        if (rc == GCN_OK) {
+            Epi ep{a.epilogue == kEpiRelu ? kActRelu : kActNone, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
+            const int64_t quads = a.n * (a.cols / 4);
+            k_join_parts<<<dim3((unsigned)((quads + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+                static_cast<float *>(a.out), a.ld_out, a.tile_sums, a.cols, a.dinv, a.n, a.cols, ep);
+            rc = hip_status(hipGetLastError(), "k_join_parts launch");
+        }
     }
     timing_end(st);
     return rc;

@@ -342,7 +342,7 @@ int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_
     return GCN_OK;
 }
 
-int tiles_launch(const SpmmArgs &a, hipStream_t st) {
+int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, bool beside_gather, hipStream_t st) {
     if (a.t_dtype != GCN_F32 || a.out_dtype != GCN_F32 || a.cols > 256) {
         set_error("dense tiles: float32 matrices of at most 256 columns only");
         return GCN_EINVAL;
@@ -350,22 +350,26 @@ int tiles_launch(const SpmmArgs &a, hipStream_t st) {
     const int n_rt = (int)a.n_rt;
     const unsigned grid = (unsigned)((n_rt + kXcds - 1) / kXcds * kXcds);
     const float *t = static_cast<const float *>(a.t);
-    float *out = static_cast<float *>(a.out);
+    float *out = dst;
     const bool narrow = (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * sizeof(float) <= 0xffffffffull;
 #define GCN_TILES(CB, WB, OCC)                                                                                        \
     do {                                                                                                              \
         if (narrow)                                                                                                   \
             k_tiles<float, CB, WB, true, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                 \
-                a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, a.ld_out, a.cols);                         \
+                a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, ld_dst, a.cols);                         \
         else                                                                                                          \
             k_tiles<float, CB, WB, false, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                \
-                a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, a.ld_out, a.cols);                         \
+                a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, ld_dst, a.cols);                         \
     } while (0)
     // Measured on a 47.5 k-vertex partition with 43 k dense tiles: four column blocks per wave at two waves per
     // SIMD beat one wave per SIMD (a second workgroup covers the first one's start and end) and two blocks per wave.
     if (a.cols <= 32) GCN_TILES(1, 1, 4);
     else if (a.cols <= 64) GCN_TILES(2, 1, 3);
-    else if (a.cols <= 128) GCN_TILES(4, 1, 2);
+    else if (a.cols <= 128) {
+        // beside the gather kernel the smaller form (174 registers, 16 KB of LDS) finds room on a CU sooner
+        if (beside_gather) GCN_TILES(2, 2, 3);
+        else GCN_TILES(4, 1, 2);
+    }
     else GCN_TILES(4, 2, 2);
 #undef GCN_TILES
     GCN_LAUNCH_CHECK();

@@ -27,7 +27,7 @@ def knobs(B):
         touched.append(name)
         B.gcn_set_tunable(name, value)
     yield set_
-    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1}
+    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1, "spmm_overlap": 1}
     for name in touched:
         B.gcn_set_tunable(name, defaults[name])
 
@@ -138,6 +138,27 @@ def test_aggregate_with_tiles_matches_oracle(B, oracle, knobs, case, width):
         H.assert_close(got16, ref, rtol=H.RTOL_BF16, what="bf16 on a tiled graph")
 
 
+@pytest.mark.parametrize("width", [41, 128, 256])
+def test_tile_product_beside_the_gather_kernel_or_before_it(B, oracle, knobs, width):
+    """The two ways of running the two parts give the same sums (up to their order), run after run."""
+    wl = workloads.reddit_partition(scale=0.1)
+    knobs("spmm_tiles", 1)
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    x = rng.normal_f32(width, 6, wl.n * width).reshape(wl.n, width)
+    xd = torch.from_numpy(x).cuda()
+    ref = oracle.aggregate(og, x)
+    out = {}
+    for overlap in (1, 0):
+        knobs("spmm_overlap", overlap)
+        runs = [B.gcn_aggregate(g, xd).cpu().numpy() for _ in range(4)]       # back to back: buffers and events reused
+        for r in runs[1:]:
+            np.testing.assert_array_equal(r, runs[0])
+        H.assert_close(runs[0], ref, what="overlap %d, width %d" % (overlap, width))
+        out[overlap] = runs[0]
+    np.testing.assert_allclose(out[1], out[0], rtol=0, atol=4e-6 * np.abs(ref).max())
+
+
 def test_automatic_choice(B, knobs):
     """Default rule: tiles in use when they hold at least a quarter of the entries."""
     dense = H.gpu_graph(B, workloads.reddit_partition(scale=0.1))
@@ -159,7 +180,8 @@ def test_full_step_with_tiles(B, oracle, knobs, dropout_p):
     knobs("tile_min_entries", 64)
     g = H.gpu_graph(B, wl)
     assert B.gcn_graph_tile_info(g)["in_use"]
-    for cache_ax in (0, 2):
+    for cache_ax, overlap in ((0, 1), (2, 1), (0, 0)):
+        knobs("spmm_overlap", overlap)
         _, gpu = H.gpu_epoch(B, g, wl, dropout_p=dropout_p, seed=5, cache_ax=cache_ax)
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=dropout_p, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new)
