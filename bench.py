@@ -151,8 +151,9 @@ def main() -> int:
         achieved = gather_bytes(E, n, dom_w, esize) / avg / 1e6
         tiled = tile_info["in_use"] and esize == 4
         roofline = {"bound": "hbm",
-                    "kernel": ("aggregation, width %d: k_tiles (dense 32x32 tiles on the matrix cores) followed by "
-                               "k_spmm_phased | k_spmm_wave + k_spmm_group (residual entries), timed as one"
+                    "kernel": ("aggregation, width %d: k_tiles (dense 32x32 tiles on the matrix cores) beside "
+                               "k_spmm_phased | k_spmm_wave + k_spmm_group (residual entries), then k_join_parts; "
+                               "timed as one"
                                if tiled else
                                "aggregation, width %d: k_spmm_phased | k_spmm_wave + k_spmm_group") % dom_w,
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -94,13 +94,14 @@ int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_trai
  * matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The split is used for
  * float32 matrices when the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this
  * rule, 0 never, 1 whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off
- * per call).  Sums are float32 either way; only their order differs.  With the split in use the tile product runs
- * on a stream of default priority that the graph owns, beside the gather kernel on the caller's stream (fork and
- * join by events, so the caller's stream order is kept); a third
- * launch adds the two parts (tunable "spmm_overlap": 1 this, 0 one launch after the other on the caller's stream).
- * Because that stream and its events belong to the graph, calls that aggregate over one graph (gcn_aggregate,
- * gcn_model_create, gcn_forward, gcn_backward) must not overlap in time, whatever streams they are given.  A non-finite value in a row of the
+ * per call).  Sums are float32 either way; only their order differs.  A non-finite value in a row of the
  * aggregated matrix reaches, through 0 x inf, all 32 rows of the tiles that cover it.
+ * Streams: with the split in use the tile product runs on a stream of default priority that the graph owns,
+ * beside the gather kernel on the caller's stream; fork and join are done with events, so the caller's stream
+ * order is kept, and a third launch adds the two parts.  Tunable "spmm_overlap": 1 = this (default), 0 = one
+ * launch after the other on the caller's stream.  Because that stream and its events belong to the graph, calls that aggregate over one graph
+ * (gcn_aggregate, gcn_model_create, gcn_forward, gcn_backward) must not overlap in time, whatever streams they
+ * are given.
  * gcn_graph_tile_info: number of dense tiles, stored entries inside them, 1 if the split is in use.
  * gcn_graph_get_tiles (only when in use; any pointer may be NULL; asynchronous on `stream` except *res_nnz):
  *   tile_ptr [dev, ceil(n/32)+1 int64]  dense tiles of row tile i are tile_ptr[i] .. tile_ptr[i+1]
