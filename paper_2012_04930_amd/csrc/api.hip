@@ -207,7 +207,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     int pw = 0, pr = 0;
     const bool phased = phased_shape(n, &pw, &pr);   // (a null pointer says nothing here: a measuring Carver returns null)
-    g.pb.prow = phased ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
+    g.pb.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
     g.pb.flags = c.take<int32_t>(16);
     TileBuffers &tb = g.tiles;
@@ -225,7 +225,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.deg = c.take<int32_t>(n);
     g.res.perm = c.take<int32_t>(n);
     g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
-    g.res.prow = phased ? c.take<int32_t>((size_t)kColBlocks * pw * pr) : nullptr;
+    g.res.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
     g.res.flags = c.take<int32_t>(16);
     g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
     g.labels = c.take<int32_t>(n);

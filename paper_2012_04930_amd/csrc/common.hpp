@@ -40,8 +40,9 @@ constexpr int kWave = 64;
 constexpr int kLdAlign = 16;   // leading dimensions are multiples of 16 elements (64 B in fp32)
 constexpr int kColSlack = 64;  // readable entries after the last column index (index prefetch runs one step ahead)
 constexpr int kHeavyDegree = 32;  // rows with at least this many entries get a whole wave in the aggregation
-constexpr int kColBlocks = 8;     // column ranges of the phased aggregation schedule, one per XCD
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
+constexpr int kRangesPerXcd = 2;  // column ranges of the phased aggregation schedule per XCD
+constexpr int kColBlocks = kXcds * kRangesPerXcd;
 constexpr int kTileMinEntriesFloor = 64;   // a dense 32 x 32 tile holds at least this many entries (bounds their number)
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -76,7 +77,7 @@ struct PrepBuffers {
     // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
     int32_t *segoff;   // n * (kColBlocks + 1)
     // phased schedule (only for graphs small enough for it, else unused): rows of each wave, see phased_shape()
-    int32_t *prow;     // kColBlocks * W * R
+    int32_t *prow;     // kXcds * W * R
     // scratch
     int32_t *scratch;  // nnz_in + n
     int32_t *heavy;    // n   1 if the row is heavy
@@ -90,11 +91,11 @@ int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_
 int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, PrepBuffers &pb,
                    hipStream_t st);
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
-// Phased aggregation schedule: each XCD owns one of kColBlocks id ranges, each of its W waves R rows.
+// Phased aggregation schedule: each XCD owns the rows of one of kXcds equal id ranges, each of its W waves R rows.
 // false when the graph is too large for it: more than 8 rows per wave with 896 waves per XCD (32 CUs x 4 SIMDs x
 // 7 waves, what the kernel's register use lets be resident at once; the schedule wants the whole grid resident).
 inline bool phased_shape(int64_t n, int *W, int *R) {
-    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+    const int64_t block = (n + kXcds - 1) / kXcds;
     const int64_t need = (block + 895) / 896;
     if (need > 8) return false;
     *R = need <= 4 ? 4 : (need <= 6 ? 6 : 8);

@@ -407,12 +407,12 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
 }
 
 int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st) {
-    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+    const int64_t block = (n + kXcds - 1) / kXcds;
     if (block > kMaxRangeRows) {
         set_error("phased schedule: more than %d rows per range", kMaxRangeRows);
         return GCN_EINVAL;
     }
-    k_balance_rows<<<dim3(kColBlocks), dim3(kThreads), 0, st>>>(n, block, deg, W, R, prow);
+    k_balance_rows<<<dim3(kXcds), dim3(kThreads), 0, st>>>(n, block, deg, W, R, prow);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

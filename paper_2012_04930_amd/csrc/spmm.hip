@@ -191,10 +191,11 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
 
 // ------------------------------------------------------------------------------------------------ phased schedule
 // For inputs a few times larger than one L2 (one partition of a distributed graph is that size): the vertex ids
-// are cut into kColBlocks equal ranges.  XCD x owns the rows of range x; each of its waves owns R consecutive
-// rows for the whole kernel and keeps their sums in registers.  The work goes in kColBlocks phases: in phase s
-// every wave of XCD x adds, for each of its rows, the entries whose columns lie in range (x + s) mod kColBlocks
-// (rows are sorted, so that is one contiguous segment, found through segoff).  All waves start together and
+// are cut into kXcds equal row ranges and each of those into kRangesPerXcd column ranges.  XCD x owns the rows of
+// row range x; each of its waves owns R rows for the whole kernel and keeps their sums in registers.  The work
+// goes in kColBlocks phases: in phase s every wave of XCD x adds, for each of its rows, the entries whose columns
+// lie in column range (kRangesPerXcd (x + 1) + s) mod kColBlocks, so the XCDs are always kRangesPerXcd ranges apart
+// and each ends on its own rows' ranges (rows are sorted, so a range is one contiguous segment, found through segoff).  All waves start together and
 // carry similar loads (rows are dealt to waves by degree, in serpentine order), so for a while an XCD's gathers
 // fall into one range (about 3 MB of the input), which its L2 holds: most entries outside a row's own
 // neighbourhood stop missing.  There is no synchronisation of any kind: a row never leaves its wave, and waves
@@ -229,8 +230,8 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
         for (int i = 0; i < V; ++i) acc[j][i] = 0.0f;
     // the ranges other than the wave's own come first: they are short, and right after the common start all
     // waves still move in step; the long pass over the own range (its rows' neighbourhood) ends the kernel
-    for (int s = 1; s <= kColBlocks; ++s) {
-        const int b = (x + s) % kColBlocks;
+    for (int s = 0; s < kColBlocks; ++s) {
+        const int b = (kRangesPerXcd * (x + 1) + s) % kColBlocks;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const int64_t r = rows[j];
