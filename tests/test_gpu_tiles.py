@@ -185,3 +185,47 @@ def test_full_step_with_tiles(B, oracle, knobs, dropout_p):
         _, gpu = H.gpu_epoch(B, g, wl, dropout_p=dropout_p, seed=5, cache_ax=cache_ax)
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=dropout_p, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+def test_epoch_captured_in_a_hip_graph_replays_like_eager_launches(B, knobs):
+    """The fork to the graph's own stream and the join back are ordinary event edges, so a caller may capture an
+    epoch.  Every replay is compared with the eager epoch of the same number; eager work runs between replays."""
+    wl = workloads.reddit_partition(scale=0.08)
+    knobs("spmm_tiles", 1)
+    g = H.gpu_graph(B, wl)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+
+    def make():
+        m = B.gcn_model_create(g, wl.dims)
+        B.gcn_set_weights(m, wl.weights)
+        return m
+
+    def epoch(m):
+        B.gcn_forward(m, True)
+        B.gcn_loss_acc(m, sync=False)
+        B.gcn_backward(m)
+        B.gcn_sgd_step(m, wl.lr)
+
+    def weights(m):
+        torch.cuda.synchronize()
+        return [B.gcn_get_tensor(m, B.GCN_T_W, l).cpu().numpy() for l in (1, 2)]
+
+    eager, want = make(), []
+    for _ in range(4):
+        epoch(eager)
+        want.append(weights(eager))
+
+    replayed = make()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    cg = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(cg, stream=side):
+        epoch(replayed)                       # recorded, not run
+    x = torch.from_numpy(rng.normal_f32(3, 3, wl.n * 16).reshape(wl.n, 16)).cuda()
+    for k in range(4):
+        cg.replay()
+        got = weights(replayed)
+        for a, b in zip(got, want[k]):
+            np.testing.assert_array_equal(a, b)
+        B.gcn_aggregate(g, x)                 # eager work on the same graph between replays
+        torch.cuda.synchronize()
