@@ -32,28 +32,6 @@ def knobs(B):
         B.gcn_set_tunable(name, defaults[name])
 
 
-def tile_split(n, rowptr, col, min_entries):
-    """The definition: count the stored entries of every aligned 32 x 32 tile of the canonical pattern; tiles with at
-    least min_entries are dense.  -> tile_ptr, tile_col, bits [n_tiles x 32] (uint32), res_rowptr, res_col"""
-    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
-    n_rt = (n + 31) // 32
-    key = (rows // 32) * n_rt + col // 32
-    uniq, inverse, cnt = np.unique(key, return_inverse=True, return_counts=True)
-    dense = cnt >= min_entries
-    dkeys = uniq[dense]                                     # ascending: by row tile, then column tile
-    tile_ptr = np.zeros(n_rt + 1, dtype=np.int64)
-    np.cumsum(np.bincount(dkeys // n_rt, minlength=n_rt), out=tile_ptr[1:])
-    tile_col = (dkeys % n_rt).astype(np.int32)
-    in_dense = dense[inverse]
-    tile_of_entry = np.cumsum(dense)[inverse] - 1            # index among the dense tiles
-    bits = np.zeros((len(dkeys), 32), dtype=np.uint32)
-    np.bitwise_or.at(bits, (tile_of_entry[in_dense], rows[in_dense] % 32),
-                     (np.uint32(1) << (col[in_dense] % 32).astype(np.uint32)))
-    res_rowptr = np.zeros(n + 1, dtype=np.int64)
-    np.cumsum(np.bincount(rows[~in_dense], minlength=n), out=res_rowptr[1:])
-    return tile_ptr, tile_col, bits, res_rowptr, col[~in_dense].astype(np.int32), int(in_dense.sum())
-
-
 def _complete_blocks(n, block):
     """Disjoint cliques of `block` vertices (the last one smaller): every tile inside a clique is full."""
     u, v = [], []
@@ -80,7 +58,7 @@ def test_tile_split_is_bit_exact(B, oracle, knobs, case):
     knobs("tile_min_entries", thr)
     g = H.gpu_graph(B, wl)
     og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
-    want = tile_split(wl.n, og.rowptr, og.col, thr)
+    want = H.tile_split(wl.n, og.rowptr, og.col, thr)
     info = B.gcn_graph_tile_info(g)
     assert info["in_use"] and info["n_tiles"] == len(want[1]) and info["nnz_dense"] == want[5] > 0
     got = [t.cpu().numpy() for t in B.gcn_graph_get_tiles(g)]
