@@ -253,6 +253,58 @@ int gcn_xcc_ids(int32_t *out, int32_t n_blocks, void *stream);
  * collected for the library's kernels are scaled by what they report for this one.  Asynchronous. */
 int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------------------------
+ * GraphSAGE with the element-wise mean as propagation rule, two layers, trained in batches (Section 4.1: sample a
+ * fixed number of neighbours, aggregate their features, predict; batch size 256, Adam).  Per batch of B target
+ * vertices, with N(v) = the row of v in the graph without v itself:
+ *   level-1 instances  m = i (1 + S2) + t:  t = 0 the target batch[i] itself, t = 1..S2 its sampled neighbours
+ *   h_m  = relu(W1^T [x_u | (1 / S1) sum of the S1 sampled rows of X])          u = the vertex of instance m
+ *   z_i  = W2^T [h_(i,0) | (1 / S2) sum over t = 1..S2 of h_(i,t)]              logits of target i
+ *   loss = softmax cross-entropy averaged over the batch (labels of the graph), Section 2.2
+ * Where the paper is silent: own row and mean are concatenated; no normalisation of embeddings; neighbours are
+ * drawn uniformly with replacement (always S draws; a vertex without neighbours contributes zeros); instances are
+ * not deduplicated; draw j of instance m at level l (1 = outer, S1; 2 = the targets' own, S2) is neighbour number
+ * floor(u d) of the d sorted neighbours, u = top 32 bits of mix(key_l + (m S + j) g) / 2^32, g = 0x9E3779B97F4A7C15,
+ * mix(z) = the SplitMix64 output function of z + g, key_l = mix(mix(seed) ^ step * 0xD1B54A32D192ED03 ^
+ * l * 0x8CB92BA72F3D8DD7).  The graph must store float32 features (GCN_F32); at most 256 hidden units and classes.
+ * Weights, caller layout: w1 [2 f x hidden] row-major (rows 0..f-1 multiply the vertex's own features, rows
+ * f..2f-1 the mean), w2 [2 hidden x classes] likewise.  All device pointers; calls are asynchronous on `stream`
+ * except where noted.  The workspace (gcn_sage_workspace_bytes, 256-byte aligned) belongs to the object until
+ * gcn_sage_destroy; the graph must outlive it.  Errors: GCN_EINVAL, GCN_EWORKSPACE, GCN_EHIP. */
+typedef struct gcn_sage gcn_sage;
+int gcn_sage_workspace_bytes(const gcn_graph *g, int32_t hidden, int32_t s1, int32_t s2, int32_t max_batch,
+                             size_t *bytes);
+int gcn_sage_create(gcn_sage **out, const gcn_graph *g, int32_t hidden, int32_t s1, int32_t s2, int32_t max_batch,
+                    uint64_t seed, void *workspace, size_t workspace_bytes, void *stream);
+int gcn_sage_destroy(gcn_sage *s);
+/* Also clears the Adam moments and the step count. */
+int gcn_sage_set_weights(gcn_sage *s, const float *w1, const float *w2, void *stream);
+/* Samples (key from the object's seed and `step`), both layers.  batch [dev, n_batch int32, 1 <= n_batch <=
+ * max_batch, entries in [0, n), repeats allowed] is copied.  Synchronous (the range check is read back). */
+int gcn_sage_forward(gcn_sage *s, const int32_t *batch, int32_t n_batch, uint64_t step, void *stream);
+/* Loss, accuracy = correct / n_batch, number of correct arg-max predictions (ties: lowest class) of the last
+ * forward; also leaves dLoss/dlogits for gcn_sage_backward.  loss, acc, correct [host] may be NULL; if all are,
+ * the call is asynchronous. */
+int gcn_sage_loss_acc(gcn_sage *s, float *loss, float *acc, int64_t *correct, void *stream);
+int gcn_sage_backward(gcn_sage *s, void *stream);
+/* Adam (Kingma & Ba) on both weight matrices, bias-corrected, step count kept by the object. */
+int gcn_sage_adam_step(gcn_sage *s, float lr, float beta1, float beta2, float eps, void *stream);
+enum {
+    GCN_SAGE_W1 = 0,       /* float [2 f x hidden]                                              */
+    GCN_SAGE_W2 = 1,       /* float [2 hidden x classes]                                        */
+    GCN_SAGE_DW1 = 2,      /* float [2 f x hidden]            after gcn_sage_backward           */
+    GCN_SAGE_DW2 = 3,      /* float [2 hidden x classes]      after gcn_sage_backward           */
+    GCN_SAGE_H1 = 4,       /* float [n_batch (1 + S2) x hidden]   layer-1 outputs, instance order */
+    GCN_SAGE_LOGITS = 5,   /* float [n_batch x classes]                                          */
+    GCN_SAGE_C1_MEAN = 6,  /* float [n_batch (1 + S2) x f]    the mean of the sampled feature rows */
+    GCN_SAGE_INNER = 7,    /* int32 [n_batch x S2]            sampled neighbours of the targets, -1 = none */
+    GCN_SAGE_OUTER = 8     /* int32 [n_batch (1 + S2) x S1]   sampled neighbours of the instances */
+};
+/* Copies one of the above (of the last batch) to dst [dev, dst_elems elements of its type]. */
+int gcn_sage_get_tensor(gcn_sage *s, int which, void *dst, size_t dst_elems, void *stream);
+/* Pseudo-width under which gcn_timing_read reports the launches of the feature gather (k_sage_concat1). */
+#define GCN_TIMING_SAGE_GATHER (-1)
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,8 @@ EXPORTS = [
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
     "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
     "gcn_augment_workspace_bytes", "gcn_augment_partition", "gcn_gather_rows", "gcn_average_weights", "gcn_xcc_ids",
+    "gcn_sage_workspace_bytes", "gcn_sage_create", "gcn_sage_destroy", "gcn_sage_set_weights", "gcn_sage_forward",
+    "gcn_sage_loss_acc", "gcn_sage_backward", "gcn_sage_adam_step", "gcn_sage_get_tensor",
 ]
 
 _lib = None
@@ -71,6 +73,15 @@ def lib():
         L.gcn_loss_acc_counts.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), vp]
         L.gcn_backward.argtypes = [vp, vp]
         L.gcn_sgd_step.argtypes = [vp, C.c_float, vp]
+        L.gcn_sage_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz)]
+        L.gcn_sage_create.argtypes = [C.POINTER(vp), vp, i32, i32, i32, i32, C.c_uint64, vp, sz, vp]
+        L.gcn_sage_destroy.argtypes = [vp]
+        L.gcn_sage_set_weights.argtypes = [vp, vp, vp, vp]
+        L.gcn_sage_forward.argtypes = [vp, vp, i32, C.c_uint64, vp]
+        L.gcn_sage_loss_acc.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i64), vp]
+        L.gcn_sage_backward.argtypes = [vp, vp]
+        L.gcn_sage_adam_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float, vp]
+        L.gcn_sage_get_tensor.argtypes = [vp, C.c_int, vp, sz, vp]
         L.gcn_timing_enable.argtypes = [C.c_int]
         L.gcn_timing_reset.argtypes = []
         L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
@@ -346,4 +357,80 @@ def gcn_average_weights(models) -> None:
 def gcn_xcc_ids(n_blocks: int) -> torch.Tensor:
     out = torch.empty(n_blocks, dtype=torch.int32, device="cuda")
     _check(lib().gcn_xcc_ids(out.data_ptr(), n_blocks, _stream()))
+    return out
+
+
+# ---------------------------------------------------------------------------------------------- GraphSAGE-mean
+GCN_SAGE_W1, GCN_SAGE_W2, GCN_SAGE_DW1, GCN_SAGE_DW2, GCN_SAGE_H1, GCN_SAGE_LOGITS, GCN_SAGE_C1_MEAN, \
+    GCN_SAGE_INNER, GCN_SAGE_OUTER = range(9)
+GCN_TIMING_SAGE_GATHER = -1
+
+
+class Sage:
+    """Owns the GraphSAGE handle and its workspace; keeps the graph alive."""
+
+    def __init__(self, handle, ws, graph, hidden, s1, s2, max_batch):
+        self.handle, self.ws, self.graph = handle, ws, graph
+        self.hidden, self.s1, self.s2, self.max_batch = hidden, s1, s2, max_batch
+        self.n_batch = 0
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gcn_sage_destroy(self.handle)
+            self.handle = None
+
+
+def gcn_sage_create(g: Graph, hidden: int, s1: int, s2: int, max_batch: int, seed: int = 0) -> Sage:
+    L = lib()
+    need = C.c_size_t()
+    _check(L.gcn_sage_workspace_bytes(g.handle, hidden, s1, s2, max_batch, C.byref(need)))
+    ws = _workspace(need.value)
+    h = C.c_void_p()
+    _check(L.gcn_sage_create(C.byref(h), g.handle, hidden, s1, s2, max_batch, seed, ws.data_ptr(), ws.numel(),
+                             _stream()))
+    return Sage(h, ws, g, hidden, s1, s2, max_batch)
+
+
+def gcn_sage_set_weights(s: Sage, w1, w2) -> None:
+    w1 = torch.as_tensor(w1, dtype=torch.float32).contiguous().cuda()
+    w2 = torch.as_tensor(w2, dtype=torch.float32).contiguous().cuda()
+    assert tuple(w1.shape) == (2 * s.graph.f, s.hidden) and tuple(w2.shape) == (2 * s.hidden, s.graph.n_classes)
+    _check(lib().gcn_sage_set_weights(s.handle, w1.data_ptr(), w2.data_ptr(), _stream()))
+    torch.cuda.current_stream().synchronize()       # w1, w2 may be temporaries
+
+
+def gcn_sage_forward(s: Sage, batch: torch.Tensor, step: int) -> None:
+    _check(lib().gcn_sage_forward(s.handle, _dev(batch, torch.int32), batch.numel(), step, _stream()))
+    s.n_batch = batch.numel()
+
+
+def gcn_sage_loss_acc(s: Sage, sync: bool = True):
+    if not sync:
+        _check(lib().gcn_sage_loss_acc(s.handle, None, None, None, _stream()))
+        return None
+    loss, acc, correct = C.c_float(), C.c_float(), C.c_int64()
+    _check(lib().gcn_sage_loss_acc(s.handle, C.byref(loss), C.byref(acc), C.byref(correct), _stream()))
+    return loss.value, acc.value, correct.value
+
+
+def gcn_sage_backward(s: Sage) -> None:
+    _check(lib().gcn_sage_backward(s.handle, _stream()))
+
+
+def gcn_sage_adam_step(s: Sage, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    _check(lib().gcn_sage_adam_step(s.handle, lr, beta1, beta2, eps, _stream()))
+
+
+def gcn_sage_get_tensor(s: Sage, which: int) -> torch.Tensor:
+    f, h, c, B = s.graph.f, s.hidden, s.graph.n_classes, s.n_batch
+    n1 = B * (1 + s.s2)
+    shape, dt = {
+        GCN_SAGE_W1: ((2 * f, h), torch.float32), GCN_SAGE_DW1: ((2 * f, h), torch.float32),
+        GCN_SAGE_W2: ((2 * h, c), torch.float32), GCN_SAGE_DW2: ((2 * h, c), torch.float32),
+        GCN_SAGE_H1: ((n1, h), torch.float32), GCN_SAGE_LOGITS: ((B, c), torch.float32),
+        GCN_SAGE_C1_MEAN: ((n1, f), torch.float32), GCN_SAGE_INNER: ((B, s.s2), torch.int32),
+        GCN_SAGE_OUTER: ((n1, s.s1), torch.int32),
+    }[which]
+    out = torch.empty(shape, dtype=dt, device="cuda")
+    _check(lib().gcn_sage_get_tensor(s.handle, which, out.data_ptr(), out.numel(), _stream()))
     return out

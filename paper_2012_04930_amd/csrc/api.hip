@@ -8,6 +8,7 @@
 #include <string>
 
 #include "common.hpp"
+#include "graph_object.hpp"
 
 namespace gcn {
 
@@ -80,29 +81,6 @@ void timing_end(hipStream_t st) {
 using namespace gcn;
 
 // ------------------------------------------------------------------------------------------- objects
-struct gcn_graph {
-    int64_t n = 0, nnz_in = 0, E = 0, n_heavy = 0, n_train = 0;
-    int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
-    int store_dtype = GCN_F32;
-    PrepBuffers pb{};
-    // dense tiles and the residual pattern beside them (in use only when the tiles hold enough of the entries)
-    TileBuffers tiles{};
-    PrepBuffers res{};
-    int64_t n_tiles = 0, nnz_dense = 0, res_n_heavy = 0;
-    bool use_tiles = false;
-    // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's
-    hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    ~gcn_graph() {
-        if (ev_fork) (void)hipEventDestroy(ev_fork);
-        if (ev_join) (void)hipEventDestroy(ev_join);
-        if (side) (void)hipStreamDestroy(side);
-    }
-    void *x = nullptr;           // (n + 1) x ldf elements of store_dtype, zero padded, last row zero
-    int32_t *labels = nullptr;
-    uint8_t *mask = nullptr;
-};
-
 struct Layer {
     int d_in, d_out, ld_in, ld_out;
     float *w;    // ld_in x ld_out
