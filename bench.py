@@ -45,6 +45,77 @@ def read_traffic(workload: str, width: int):
     return None
 
 
+def sage_leg(B, torch, np, g, wl, args, cpu_baseline):
+    """One pass over the train vertices in batches of 256 (hidden 128, S1 = 25, S2 = 10, Adam lr 1e-4): sample,
+    both layers, loss, backward, update per batch.  Batches come from a seeded permutation, resident in HBM."""
+    from synth import rng
+    hidden, s1, s2, bsz = 128, 25, 10, 256
+    f, classes = wl.x.shape[1], wl.dims[-1]
+    model = B.gcn_sage_create(g, hidden, s1, s2, bsz, seed=args.seed)
+    a1, a2 = np.sqrt(6.0 / (2 * f + hidden)), np.sqrt(6.0 / (2 * hidden + classes))
+    w1 = ((rng.uniform(args.seed, 901, 2 * f * hidden) * 2 - 1) * a1).astype(np.float32).reshape(2 * f, hidden)
+    w2 = ((rng.uniform(args.seed, 902, 2 * hidden * classes) * 2 - 1) * a2).astype(np.float32).reshape(2 * hidden, classes)
+    B.gcn_sage_set_weights(model, w1, w2)
+    train = np.nonzero(wl.mask)[0]
+    order = train[rng.permutation(args.seed, 903, len(train))].astype(np.int32)
+    batches = [torch.from_numpy(order[i:i + bsz]).cuda() for i in range(0, len(order), bsz)]
+
+    def one_pass(first_step):
+        for k, b in enumerate(batches):
+            B.gcn_sage_forward(model, b, first_step + k)
+            B.gcn_sage_loss_acc(model, sync=False)
+            B.gcn_sage_backward(model)
+            B.gcn_sage_adam_step(model, 1e-4)
+
+    one_pass(0)                                        # warm-up pass
+    torch.cuda.synchronize()
+    B.gcn_timing_reset()
+    B.gcn_timing_enable(True)
+    t0 = time.perf_counter()
+    one_pass(len(batches))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    B.gcn_timing_enable(False)
+    cnt, ms = B.gcn_timing_read(B.GCN_TIMING_SAGE_GATHER)
+    n1 = bsz * (1 + s2)
+    ldf = (f + 15) // 16 * 16
+    # algorithmic bytes of one full-batch gather: (1 + S1) feature rows read per instance, ids, two rows written
+    by = n1 * ((1 + s1) * f * 4 + (1 + s1) * 4 + 2 * ldf * 4)
+    full = [1 for b in batches if b.numel() == bsz]
+    avg = ms / cnt if cnt else float("nan")
+    out = {"workload": wl.name, "hidden": hidden, "S1": s1, "S2": s2, "batch": bsz, "batches": len(batches),
+           "lr": 1e-4, "ms_per_batch": round(1e3 * wall / len(batches), 4),
+           "epochs_per_s": round(1.0 / wall, 3), "targets_per_s": round(len(order) / wall, 1),
+           "gather": {"kernel": "k_sage_concat1", "bound": "hbm", "launches": cnt, "avg_launch_ms": round(avg, 5),
+                      "bytes_per_full_launch": by,
+                      "achieved": round(by * len(full) / max(len(batches), 1) / avg / 1e6, 1) if cnt else None,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s"}}
+    if out["gather"]["achieved"]:
+        out["gather"]["frac"] = round(out["gather"]["achieved"] / HBM_PEAK_GBS, 4)
+    if cpu_baseline:
+        from oracle import gcn_oracle as O
+        from oracle import sage_oracle as SO
+        og = O.canonicalise(wl.n, wl.rowptr, wl.col)
+        ws, state = [w1.astype(np.float64), w2.astype(np.float64)], {}
+        t0 = time.perf_counter()
+        done = 0
+        for k in range(len(batches)):
+            b = order[k * bsz:(k + 1) * bsz]
+            t = SO.forward(og.rowptr, og.col, wl.x, ws[0], ws[1], b, s1, s2, args.seed, k)
+            d1, d2 = SO.backward(t, ws[1], wl.labels[b], s2)
+            ws = O.adam(ws, [d1, d2], state, 1e-4)
+            done += 1
+            if time.perf_counter() - t0 > 10.0:
+                break
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(done / dt, 3), "unit": "batches/s", "kind": "oracle",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "sample": "%d batches of %d in %.1f s (numpy fp64)" % (done, bsz, dt),
+                               "gpu_batches_per_s": round(len(batches) / wall, 1)}
+    del model
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +130,9 @@ def main() -> int:
                     help="also run one plain copy kernel of this many MiB (scales rocprofv3 byte counters)")
     ap.add_argument("--no-alt-mode", action="store_true", help="skip the second timed run with the cache_ax switch flipped")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket aggregation launches with events")
+    ap.add_argument("--sage", action="store_true",
+                    help="also time the second network of the paper, GraphSAGE-mean in batches of 256 (Section 4.1), "
+                         "over one pass of the train vertices; reported under \"sage\" in the same line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one partition = one worker's share of the "
@@ -175,6 +249,10 @@ def main() -> int:
                  "epochs_per_s": round(args.steps / max(w2, e2 / 1e3), 3)}
         del m2
 
+    sage = None
+    if args.sage and dtype == B.GCN_F32:
+        sage = sage_leg(B, torch, np, g, wl, args, not args.no_cpu_baseline)
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import gcn_oracle as O
@@ -204,7 +282,7 @@ def main() -> int:
                    "lr": wl.lr, "optimizer": args.optimizer, "seed": args.seed, "layer1_from_cached_AX": default_cached,
                    "dense_tiles": tile_info},
         "other_mode": other,
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "sage": sage,
         "spmm": spmm, "final_loss": round(loss, 6), "final_acc": round(acc, 6),
         "event_ms_total": round(ev_ms, 3), "wall_s_total": round(wall, 4),
         "graph_create_s": round(t_create, 3), "generate_s": round(t_gen, 1),

@@ -280,7 +280,9 @@ int gcn_sage_destroy(gcn_sage *s);
 /* Also clears the Adam moments and the step count. */
 int gcn_sage_set_weights(gcn_sage *s, const float *w1, const float *w2, void *stream);
 /* Samples (key from the object's seed and `step`), both layers.  batch [dev, n_batch int32, 1 <= n_batch <=
- * max_batch, entries in [0, n), repeats allowed] is copied.  Synchronous (the range check is read back). */
+ * max_batch, entries in [0, n), repeats allowed] is copied.  Asynchronous, so an entry outside [0, n) cannot be
+ * refused here: it is computed as a vertex without features and neighbours, with label 0, and raises a flag that
+ * the next gcn_sage_loss_acc with a host pointer reports as GCN_EINVAL (and clears). */
 int gcn_sage_forward(gcn_sage *s, const int32_t *batch, int32_t n_batch, uint64_t step, void *stream);
 /* Loss, accuracy = correct / n_batch, number of correct arg-max predictions (ties: lowest class) of the last
  * forward; also leaves dLoss/dlogits for gcn_sage_backward.  loss, acc, correct [host] may be NULL; if all are,

@@ -227,6 +227,11 @@ int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
             const float *rowscale, const Activation *act /* may be null */, hipStream_t st);
 int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
             const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st);
+// nn for few rows: c = [relu](a b) with the shared dimension split over workgroups and the partial matrices added
+// in ascending order; partials holds gemm_nn_splitk_partial_floats(M, K, N) floats
+size_t gemm_nn_splitk_partial_floats(int64_t M, int K, int N);
+int gemm_nn_splitk(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
+                   bool relu, float *partials, size_t partial_floats, hipStream_t st);
 size_t gemm_tn_partial_floats(int64_t rows, int M, int N);
 int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t rows, int M, int N,
             float *partials, size_t partial_floats, hipStream_t st);

@@ -42,6 +42,8 @@ struct GemmArgs {
     float scale;
     int64_t rows_per_split;  // tn
     Activation act;          // nn: applied after the row scale
+    int k_per_split;         // nn: 0 = the whole shared dimension in one workgroup; else blockIdx.y takes this many k
+                             // and writes its own partial matrix (M x ldc, one after the other at c)
 };
 
 template <int MODE, int WM, int WN, int TN>
@@ -73,6 +75,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
         n0 = (blockIdx.x % ntiles) * BN;
         kbeg = 0;
         kend = g.K;
+        if (MODE == kNN && g.k_per_split > 0) {
+            kbeg = (int64_t)blockIdx.y * g.k_per_split;
+            kend = kbeg + g.k_per_split < g.K ? kbeg + g.k_per_split : g.K;
+        }
     }
 
     f32x16 acc[TN];
@@ -185,6 +191,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
     const int64_t out_rows = (MODE == kTN) ? (int64_t)g.K : g.M;
     float *cbase = g.c;
     if (MODE == kTN) cbase += (int64_t)blockIdx.y * (int64_t)g.K * g.ldc;   // this split's partial matrix
+    if (MODE == kNN && g.k_per_split > 0) cbase += (int64_t)blockIdx.y * g.M * g.ldc;
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int col = n0 + (wn * TN + t) * 32 + l32;
@@ -237,6 +244,28 @@ __global__ void k_reduce_partials(const float4 *__restrict__ partials, int split
     c[i] = s;
 }
 
+// as k_reduce_partials, then max(., 0) when relu is set
+__global__ void k_reduce_partials_relu(const float4 *__restrict__ partials, int splits, size_t count4,
+                                       float4 *__restrict__ c, int relu) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count4) return;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < splits; ++p) {
+        const float4 v = partials[(size_t)p * count4 + i];
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
+    }
+    if (relu) {
+        s.x = s.x > 0.f ? s.x : 0.f;
+        s.y = s.y > 0.f ? s.y : 0.f;
+        s.z = s.z > 0.f ? s.z : 0.f;
+        s.w = s.w > 0.f ? s.w : 0.f;
+    }
+    c[i] = s;
+}
+
 template <int MODE>
 int launch_rows(GemmArgs &g, hipStream_t st) {   // nn, nt
     if (g.N > 64) {
@@ -277,8 +306,48 @@ int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
         set_error("gemm_nn: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0, act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0, act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
     return launch_rows<kNN>(g, st);
+}
+
+// For few rows: the shared dimension is split over blockIdx.y so that the chip fills, the partial matrices are
+// added in ascending order (and passed through max(., 0) if relu is set).
+int nn_splits(int64_t M, int K, int N) {
+    const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
+    int splits = (int)(512 / (tiles > 0 ? tiles : 1));
+    const int max_by_k = K / (4 * BK) > 0 ? K / (4 * BK) : 1;    // at least 64 of the shared dimension per split
+    if (splits > max_by_k) splits = max_by_k;
+    return splits < 1 ? 1 : splits;
+}
+
+size_t gemm_nn_splitk_partial_floats(int64_t M, int K, int N) {
+    return (size_t)nn_splits(M, K, N) * (size_t)M * (size_t)padded_width(N);
+}
+
+int gemm_nn_splitk(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
+                   bool relu, float *partials, size_t partial_floats, hipStream_t st) {
+    if (M <= 0) return GCN_OK;
+    if (!check_ld(lda, ldb, ldc) || K % BK != 0 || K > lda || N > ldb || N > 128 * 65535) {
+        set_error("gemm_nn_splitk: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
+        return GCN_EINVAL;
+    }
+    const int splits = nn_splits(M, K, N);
+    if ((size_t)splits * (size_t)M * (size_t)ldc > partial_floats) {
+        set_error("gemm_nn_splitk: partial buffer too small");
+        return GCN_EWORKSPACE;
+    }
+    int per = (K + splits - 1) / splits;
+    per = (per + BK - 1) / BK * BK;
+    GemmArgs g{a, lda, b, ldb, partials, ldc, M, K, N, nullptr, nullptr, 0, 1.0f, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, per};
+    const int ntiles = (N + 127) / 128;
+    const unsigned gx = (unsigned)((M + 63) / 64) * ntiles;
+    k_gemm<kNN, 2, 2, 2><<<dim3(gx, (unsigned)splits), dim3(kThreads), 0, st>>>(g);
+    GCN_LAUNCH_CHECK();
+    const size_t count4 = (size_t)M * (size_t)ldc / 4;
+    k_reduce_partials_relu<<<dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, st>>>(
+        reinterpret_cast<const float4 *>(partials), splits, count4, reinterpret_cast<float4 *>(c), relu ? 1 : 0);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
 }
 
 int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
@@ -288,7 +357,7 @@ int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
         set_error("gemm_nt: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
     return launch_rows<kNT>(g, st);
 }
 
@@ -311,7 +380,7 @@ int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
     }
     int64_t per = (rows + splits - 1) / splits;
     per = (per + BK - 1) / BK * BK;
-    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per, Activation{kActNone, 0, 0u, 1.0f, 0ull}};
+    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
     const int mtiles = (M + 127) / 128;
     if (N > 64) {
         const int ntiles = (N + 127) / 128;

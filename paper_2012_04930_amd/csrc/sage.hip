@@ -72,8 +72,9 @@ __global__ void k_sage_nodes1(const int32_t *__restrict__ batch, const int32_t *
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B * (1 + S2)) return;
     const int b = i / (1 + S2), t = i % (1 + S2);
-    nodes1[i] = t == 0 ? batch[b] : inner[b * S2 + t - 1];
-    if (t == 0) labels_b[b] = labels[batch[b]];
+    const int v = batch[b];       // already -1 if it was out of range
+    nodes1[i] = t == 0 ? v : inner[b * S2 + t - 1];
+    if (t == 0) labels_b[b] = v >= 0 ? labels[v] : 0;
 }
 
 // One thread per (instance m, four columns): c1[m] = [x_node | (1 / S1) sum over the S1 sampled rows], the sum in
@@ -174,9 +175,17 @@ __global__ void k_sage_ones(float *__restrict__ ones, uint8_t *__restrict__ mask
     }
 }
 
-__global__ void k_sage_check_batch(const int32_t *__restrict__ batch, int B, int64_t n, int32_t *flag) {
+// Copies the batch; an entry outside [0, n) becomes -1 (a vertex without features) and raises the sticky flag.
+__global__ void k_sage_take_batch(const int32_t *__restrict__ batch, int B, int64_t n, int32_t *__restrict__ own,
+                                  int32_t *flag) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B && (batch[i] < 0 || batch[i] >= n)) atomicOr(flag, 1);
+    if (i >= B) return;
+    int v = batch[i];
+    if (v < 0 || v >= n) {
+        v = -1;
+        atomicOr(flag, 1);
+    }
+    own[i] = v;
 }
 
 bool aligned(const void *p) { return ((uintptr_t)p & 255u) == 0; }
@@ -234,7 +243,9 @@ void carve_sage(Carver &c, gcn_sage &s) {
     s.mask = c.take<uint8_t>(B);
     size_t pf = gemm_tn_partial_floats((int64_t)n1, 2 * s.ldf, s.ldh);
     const size_t pf2 = gemm_tn_partial_floats((int64_t)B, 2 * s.ldh, s.ldc);
-    s.partial_floats = pf > pf2 ? pf : pf2;
+    const size_t pf3 = gemm_nn_splitk_partial_floats((int64_t)n1, 2 * s.ldf, s.ldh);
+    pf = pf > pf2 ? pf : pf2;
+    s.partial_floats = pf > pf3 ? pf : pf3;
     s.partials = c.take<float>(s.partial_floats);
     s.loss_part = c.take<double>(kLossBlocks);
     s.corr_part = c.take<long long>(kLossBlocks);
@@ -375,19 +386,10 @@ int gcn_sage_forward(gcn_sage *s, const int32_t *batch, int32_t n_batch, uint64_
     const int B = n_batch, S1 = s->s1, S2 = s->s2;
     const int64_t n1 = (int64_t)B * (1 + S2);
     s->have_forward = s->have_loss = s->have_backward = false;
-    // the batch is copied (later calls read it) and checked; the read-back makes this call synchronous
-    GCN_HIP(hipMemcpyAsync(s->batch, batch, (size_t)B * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-    int rc = fill_zero(s->flag, sizeof(int32_t), st);
-    if (rc) return rc;
-    k_sage_check_batch<<<dim3(blocks_for(B, kThreads)), dim3(kThreads), 0, st>>>(s->batch, B, g->n, s->flag);
+    // the batch is copied (later calls read it) and checked on the device; the flag is read by gcn_sage_loss_acc
+    k_sage_take_batch<<<dim3(blocks_for(B, kThreads)), dim3(kThreads), 0, st>>>(batch, B, g->n, s->batch, s->flag);
     GCN_LAUNCH_CHECK();
-    int32_t bad = 0;
-    GCN_HIP(hipMemcpyAsync(&bad, s->flag, sizeof(bad), hipMemcpyDeviceToHost, st));
-    GCN_HIP(hipStreamSynchronize(st));
-    if (bad) {
-        set_error("gcn_sage_forward: a batch entry is outside [0, %lld)", (long long)g->n);
-        return GCN_EINVAL;
-    }
+    int rc = GCN_OK;
     k_sage_sample<<<dim3(blocks_for((int64_t)B * S2, kThreads)), dim3(kThreads), 0, st>>>(
         g->pb.rowptr, g->pb.col, s->batch, B, S2, level_key(s->seed, step, 2), s->inner);
     GCN_LAUNCH_CHECK();
@@ -402,8 +404,9 @@ int gcn_sage_forward(gcn_sage *s, const int32_t *batch, int32_t n_batch, uint64_
         static_cast<const float *>(g->x), s->ldf, s->nodes1, s->outer, S1, n1, s->c1);
     timing_end(st);
     GCN_LAUNCH_CHECK();
-    const Activation relu{kActRelu, s->hidden, 0u, 1.0f, 0ull};
-    rc = gemm_nn(s->c1, 2 * s->ldf, s->w1, s->ldh, s->h1, s->ldh, n1, 2 * s->ldf, s->ldh, nullptr, &relu, st);
+    // a few thousand rows against 1216 of shared dimension: split that dimension so that the chip fills
+    rc = gemm_nn_splitk(s->c1, 2 * s->ldf, s->w1, s->ldh, s->h1, s->ldh, n1, 2 * s->ldf, s->ldh, true, s->partials,
+                        s->partial_floats, st);
     if (rc) return rc;
     k_sage_concat2<<<dim3(blocks_for((int64_t)B * (s->ldh / 4), kThreads)), dim3(kThreads), 0, st>>>(s->h1, s->ldh, B, S2,
                                                                                                      s->c2);
@@ -428,9 +431,17 @@ int gcn_sage_loss_acc(gcn_sage *s, float *loss, float *acc, int64_t *correct, vo
     if (loss || acc || correct) {
         float host[2];
         long long hc = 0;
+        int32_t bad = 0;
         GCN_HIP(hipMemcpyAsync(host, s->result, sizeof(host), hipMemcpyDeviceToHost, st));
         GCN_HIP(hipMemcpyAsync(&hc, s->result_correct, sizeof(hc), hipMemcpyDeviceToHost, st));
+        GCN_HIP(hipMemcpyAsync(&bad, s->flag, sizeof(bad), hipMemcpyDeviceToHost, st));
         GCN_HIP(hipStreamSynchronize(st));
+        if (bad) {
+            rc = fill_zero(s->flag, sizeof(int32_t), st);
+            if (rc) return rc;
+            set_error("gcn_sage_loss_acc: a batch entry since the last check was outside [0, %lld)", (long long)s->g->n);
+            return GCN_EINVAL;
+        }
         if (loss) *loss = host[0];
         if (acc) *acc = host[1];
         if (correct) *correct = (int64_t)hc;

@@ -153,13 +153,17 @@ def test_odd_shapes_and_degenerate_vertices(B, oracle, hidden, s1, s2, bsz):
 def test_errors(B, oracle):
     wl = _odd_graph()
     case = Case(B, oracle, wl, hidden=8, s1=2, s2=2, max_batch=4)
-    with pytest.raises(B.GcnError) as e:
-        B.gcn_sage_forward(case.model, torch.tensor([0, 200], dtype=torch.int32).cuda(), 0)    # vertex out of range
-    assert e.value.code == -1
-    with pytest.raises(B.GcnError):
-        B.gcn_sage_forward(case.model, torch.zeros(5, dtype=torch.int32).cuda(), 0)            # larger than max_batch
     with pytest.raises(B.GcnError):
         B.gcn_sage_backward(case.model)                                                         # nothing to differentiate
+    B.gcn_sage_forward(case.model, torch.tensor([0, 200, -3], dtype=torch.int32).cuda(), 0)    # vertices out of range:
+    assert (B.gcn_sage_get_tensor(case.model, B.GCN_SAGE_INNER).cpu().numpy()[1:] == -1).all()  # computed as empty ones
+    with pytest.raises(B.GcnError) as e:
+        B.gcn_sage_loss_acc(case.model)                                                         # ... and reported here
+    assert e.value.code == -1
+    B.gcn_sage_forward(case.model, torch.tensor([0, 1], dtype=torch.int32).cuda(), 0)
+    B.gcn_sage_loss_acc(case.model)                                                             # the flag was cleared
+    with pytest.raises(B.GcnError):
+        B.gcn_sage_forward(case.model, torch.zeros(5, dtype=torch.int32).cuda(), 0)            # larger than max_batch
     with pytest.raises(B.GcnError):
         B.gcn_sage_create(case.g, 300, 2, 2, 4)                                                 # too many hidden units
     g16 = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
