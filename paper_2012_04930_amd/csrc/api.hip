@@ -107,6 +107,7 @@ struct gcn_model {
     float *partials = nullptr;
     size_t partial_floats = 0;
     float *tile_sums = nullptr;     // n x widest aggregated matrix: the tile product's output when it runs beside the gather
+    float *chunk_sums = nullptr;    // chunks x widest: sums of the chunks of split rows
     double *loss_part = nullptr;
     long long *corr_part = nullptr;
     float *result = nullptr;        // [0] loss [1] accuracy
@@ -130,9 +131,15 @@ uint64_t host_mix64(uint64_t z) {
 
 bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
+// floats for the chunk sums of one aggregation of `cols` columns over either form of the pattern
+size_t chunk_sum_floats(const gcn_graph *g, int cols) {
+    const int64_t chunks = g->rows.n_chunks > g->res_rows.n_chunks ? g->rows.n_chunks : g->res_rows.n_chunks;
+    return (size_t)chunks * (size_t)cols;
+}
+
 // tile_sums: n x cols floats for the tile product when it runs beside the gather kernel (null: one after the other)
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
-                   int cols, int width, int epilogue, float *tile_sums) {
+                   int cols, int width, int epilogue, float *tile_sums, float *chunk_sums) {
     SpmmArgs a{};
     // the dense-tile form handles float32 matrices; everything else gathers over the whole pattern
     const bool tiles = g->use_tiles && t_dtype == GCN_F32 && out_dtype == GCN_F32 && tunable("spmm_tiles", -1) != 0;
@@ -144,7 +151,14 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
     a.segoff = pb.segoff;
     a.prow = pb.prow;
     a.n = g->n;
-    a.n_heavy = tiles ? g->res_n_heavy : g->n_heavy;
+    const gcn_graph::RowClasses &rc = tiles ? g->res_rows : g->rows;
+    a.n_heavy = rc.n_heavy;
+    a.n_light = rc.n_light;
+    a.n_split = rc.n_split;
+    a.n_chunks = rc.n_chunks;
+    a.chunk_off = pb.chunk_off;
+    a.chunk_srow = pb.chunk_srow;
+    a.chunk_sums = chunk_sums;
     if (tiles) {
         a.tile_ptr = g->tiles.tile_ptr;
         a.tile_col = g->tiles.tile_col;
@@ -182,11 +196,17 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.scratch = c.take<int32_t>(cap);
     g.pb.heavy = c.take<int32_t>(n);
     g.pb.hpos = c.take<int64_t>(n + 1);
+    g.pb.lpos = c.take<int64_t>(n + 1);
+    g.pb.split_cap = cap / kSplitDegree + 1;
+    g.pb.chunk_cap = cap / kChunk + g.pb.split_cap + 1;
+    g.pb.split_cnt = c.take<int32_t>(g.pb.split_cap);
+    g.pb.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
+    g.pb.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     int pw = 0, pr = 0;
     const bool phased = phased_shape(n, &pw, &pr);   // (a null pointer says nothing here: a measuring Carver returns null)
     g.pb.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
-    g.pb.blocksum = c.take<int64_t>(scan_blocks(n));
+    g.pb.blocksum = c.take<int64_t>(scan_blocks(n > g.pb.split_cap ? n : g.pb.split_cap));
     g.pb.flags = c.take<int32_t>(16);
     TileBuffers &tb = g.tiles;
     tb.n_rt = (n + 31) / 32;
@@ -202,6 +222,9 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.col = c.take<int32_t>(cap + kColSlack);
     g.res.deg = c.take<int32_t>(n);
     g.res.perm = c.take<int32_t>(n);
+    g.res.split_cnt = c.take<int32_t>(g.pb.split_cap);
+    g.res.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
+    g.res.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     g.res.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
     g.res.flags = c.take<int32_t>(16);
@@ -238,16 +261,15 @@ void carve_model(Carver &c, gcn_model &m) {
         m.pax = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
         m.xs = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
     }
-    m.tile_sums = nullptr;
-    if (m.g->use_tiles && m.dtype == GCN_F32) {
-        int widest = 0;
-        for (auto &ly : m.layers) widest = ly.ld_out > widest ? ly.ld_out : widest;
-        if (m.l1_cached) {   // P = A_hat X is built in slabs of 256 columns
-            const int slab = 256 < m.g->ldf ? 256 : m.g->ldf;
-            widest = slab > widest ? slab : widest;
-        }
-        m.tile_sums = c.take<float>((size_t)n * widest);
+    int widest = 0;   // columns of the widest single aggregation launch
+    for (auto &ly : m.layers) widest = ly.ld_out > widest ? ly.ld_out : widest;
+    if (m.l1_cached) {   // P = A_hat X is built in slabs of 256 (float32) or 512 (bfloat16) columns
+        const int slab_max = m.dtype == GCN_BF16 ? 512 : 256;
+        const int slab = slab_max < m.g->ldf ? slab_max : m.g->ldf;
+        widest = slab > widest ? slab : widest;
     }
+    m.tile_sums = (m.g->use_tiles && m.dtype == GCN_F32) ? c.take<float>((size_t)n * widest) : nullptr;
+    m.chunk_sums = c.take<float>(chunk_sum_floats(m.g, widest));
     m.partial_floats = pf;
     m.partials = c.take<float>(pf);
     m.loss_part = c.take<double>(kLossBlocks);
@@ -397,8 +419,16 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         return GCN_EGRAPH;
     }
     g->E = ends[0];
-    g->n_heavy = flags[4];
     g->max_deg = flags[3];
+    auto read_classes = [&](const PrepBuffers &pb, const int32_t *fl, gcn_graph::RowClasses &rc) -> hipError_t {
+        rc.n_heavy = fl[4];
+        rc.n_light = fl[5];
+        rc.n_split = n - rc.n_heavy - rc.n_light;
+        hipError_t e = hipMemcpyAsync(&rc.n_chunks, pb.chunk_off + pb.split_cap, sizeof(int64_t), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        return e;
+    };
+    HIP_OR_FAIL(read_classes(g->pb, flags, g->rows));
 
     // Dense tiles: select, then decide.  Knobs read here: "tile_min_entries" (default 128 of 1024), "spmm_tiles"
     // (-1: use the tiles when they hold at least a quarter of the entries, 0: never build, 1: whenever there is one).
@@ -429,7 +459,7 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
                 FAIL_IF(prep_balance_rows(n, g->res.deg, pw, pr, g->res.prow, st));
             HIP_OR_FAIL(hipMemcpyAsync(flags, g->res.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
             HIP_OR_FAIL(hipStreamSynchronize(st));
-            g->res_n_heavy = flags[4];
+            HIP_OR_FAIL(read_classes(g->res, flags, g->res_rows));
             HIP_OR_FAIL(hipStreamCreateWithFlags(&g->side, hipStreamNonBlocking));   // default priority
             HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_fork, hipEventDisableTiming));
             HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_join, hipEventDisableTiming));
@@ -520,6 +550,7 @@ int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, 
     c.take<float>((size_t)(g->n + 1) * ld);
     c.take<float>((size_t)(g->n + 1) * ld);
     c.take<float>((size_t)g->n * ld);
+    c.take<float>(chunk_sum_floats(g, ld));
     *bytes = c.bytes();
     return GCN_OK;
 }
@@ -543,12 +574,13 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
     float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
     float *z = c.take<float>((size_t)(g->n + 1) * ld);
     float *tile_sums = c.take<float>((size_t)g->n * ld);
+    float *chunk_sums = c.take<float>(chunk_sum_floats(g, ld));
     const size_t es = dtype == GCN_BF16 ? 2 : 4;
     rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);
     if (rc) return rc;
     rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
     if (rc) return rc;
-    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone, tile_sums);
+    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone, tile_sums, chunk_sums);
     rc = spmm_launch(a, st);
     if (rc) return rc;
     return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
@@ -684,7 +716,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
         for (int c0 = 0; !rc && c0 < g->ldf; c0 += slab) {
             const int cols = g->ldf - c0 < slab ? g->ldf - c0 : slab;
             SpmmArgs a = spmm_args(g, (const char *)m->xs + c0 * es, dtype, g->ldf, (char *)m->pax + c0 * es, dtype,
-                                   g->ldf, cols, g->f, kEpiNone, m->tile_sums);
+                                   g->ldf, cols, g->f, kEpiNone, m->tile_sums, m->chunk_sums);
             rc = spmm_launch(a, st);
         }
     }
@@ -819,7 +851,7 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
         SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
-                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums);
+                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums, m->chunk_sums);
         a.drop_threshold = act.drop_threshold;
         a.keep_scale = act.keep_scale;
         a.drop_key = act.drop_key;
@@ -899,7 +931,7 @@ int gcn_backward(gcn_model *m, void *stream) {
         }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
         SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone,
-                               m->tile_sums);
+                               m->tile_sums, m->chunk_sums);
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G

@@ -40,6 +40,8 @@ constexpr int kWave = 64;
 constexpr int kLdAlign = 16;   // leading dimensions are multiples of 16 elements (64 B in fp32)
 constexpr int kColSlack = 64;  // readable entries after the last column index (index prefetch runs one step ahead)
 constexpr int kHeavyDegree = 32;  // rows with at least this many entries get a whole wave in the aggregation
+constexpr int kSplitDegree = 4096; // rows with more entries than this are cut into chunks, one wave per chunk
+constexpr int kChunk = 2048;       // entries per chunk of a split row
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
 constexpr int kRangesPerXcd = 2;  // column ranges of the phased aggregation schedule per XCD
 constexpr int kColBlocks = kXcds * kRangesPerXcd;
@@ -71,8 +73,16 @@ struct PrepBuffers {
     int32_t *col;      // <= nnz_in + n
     int32_t *deg;      // n
     float *dinv;       // n
-    // schedule: heavy rows (degree >= kHeavyDegree) first, then light rows, each in ascending vertex order
+    // schedule: heavy rows (kHeavyDegree <= degree <= kSplitDegree) first, then light rows, then split rows (degree >
+    // kSplitDegree), each class in ascending vertex order
     int32_t *perm;     // n   slot -> row
+    // split rows: row number j of that class (perm[n_heavy + n_light + j]) owns the chunks chunk_off[j] .. chunk_off[j + 1],
+    // chunk k of it covering entries [k kChunk, (k + 1) kChunk) of the row; chunk_srow[c] = j
+    int64_t split_cap = 0, chunk_cap = 0;   // capacities (from the number of stored entries)
+    int32_t *split_cnt;   // split_cap
+    int64_t *chunk_off;   // split_cap + 1
+    int32_t *chunk_srow;  // chunk_cap
+    int64_t *lpos;     // n + 1   exclusive prefix of the light flags (scratch)
     // column blocks: the ids are cut into kColBlocks equal ranges; segoff[r * (kColBlocks + 1) + b] is the offset,
     // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
     int32_t *segoff;   // n * (kColBlocks + 1)
@@ -83,7 +93,7 @@ struct PrepBuffers {
     int32_t *heavy;    // n   1 if the row is heavy
     int64_t *hpos;     // n + 1   exclusive prefix of heavy[]
     int64_t *blocksum; // scan partials
-    int32_t *flags;    // 16 ints: [0] graph error, [1] label error, [2] n_train, [3] max degree, [4] heavy rows
+    int32_t *flags;    // 16 ints: [0] graph error, [1] label error, [2] n_train, [3] max degree, [4] heavy rows, [5] light rows
 };
 
 int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, int32_t *flags,
@@ -178,7 +188,13 @@ struct SpmmArgs {
     const int32_t *segoff;  // column-block offsets per row (see PrepBuffers)
     const int32_t *prow;    // rows per wave of the phased schedule, or null
     int64_t n;
-    int64_t n_heavy;
+    int64_t n_heavy;    // rows with a wave each
+    int64_t n_light;    // rows with a lane group each
+    int64_t n_split;    // rows cut into chunks (n_heavy + n_light + n_split = n)
+    int64_t n_chunks;
+    const int64_t *chunk_off;
+    const int32_t *chunk_srow;
+    float *chunk_sums;  // n_chunks x cols floats: the chunks' sums (workspace of the call)
     const void *t;      // float or bfloat16, ld_t elements per row, n + 1 rows
     int t_dtype;
     int ld_t;

@@ -5,14 +5,18 @@
 #include "common.hpp"
 
 struct gcn_graph {
-    int64_t n = 0, nnz_in = 0, E = 0, n_heavy = 0, n_train = 0;
+    int64_t n = 0, nnz_in = 0, E = 0, n_train = 0;
+    // row classes of the whole pattern and of the residual one: a wave each / a lane group each / cut into chunks
+    struct RowClasses {
+        int64_t n_heavy = 0, n_light = 0, n_split = 0, n_chunks = 0;
+    } rows, res_rows;
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;
     gcn::PrepBuffers pb{};
     // dense tiles and the residual pattern beside them (in use only when the tiles hold enough of the entries)
     gcn::TileBuffers tiles{};
     gcn::PrepBuffers res{};
-    int64_t n_tiles = 0, nnz_dense = 0, res_n_heavy = 0;
+    int64_t n_tiles = 0, nnz_dense = 0;
     bool use_tiles = false;
     // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's
     hipStream_t side = nullptr;

@@ -259,20 +259,49 @@ __global__ void k_dinv(int64_t n, const int32_t *__restrict__ deg, float *__rest
 }
 
 // --------------------------------------------------------------------------------------------- schedule
-__global__ void k_flag_heavy(int64_t n, const int32_t *__restrict__ deg, int32_t *__restrict__ heavy) {
+__global__ void k_flag_classes(int64_t n, const int32_t *__restrict__ deg, int32_t *__restrict__ heavy,
+                               int32_t *__restrict__ light) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) heavy[i] = deg[i] >= kHeavyDegree ? 1 : 0;
+    if (i >= n) return;
+    const int d = deg[i];
+    heavy[i] = (d >= kHeavyDegree && d <= kSplitDegree) ? 1 : 0;
+    light[i] = d < kHeavyDegree ? 1 : 0;
 }
 
-// Stable two-way partition: heavy rows keep their order in slots [0, n_heavy), light rows theirs after.
-__global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const int64_t *__restrict__ hpos,
+// Stable three-way partition: heavy rows keep their order in slots [0, n_heavy), light rows theirs after, split rows last.
+__global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const int32_t *__restrict__ light,
+                             const int64_t *__restrict__ hpos, const int64_t *__restrict__ lpos,
                              int32_t *__restrict__ perm, int32_t *flags) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const int64_t n_heavy = hpos[n];
-    const int64_t slot = heavy[i] ? hpos[i] : n_heavy + (i - hpos[i]);
+    const int64_t n_heavy = hpos[n], n_light = lpos[n];
+    int64_t slot;
+    if (heavy[i]) slot = hpos[i];
+    else if (light[i]) slot = n_heavy + lpos[i];
+    else slot = n_heavy + n_light + (i - hpos[i] - lpos[i]);
     perm[slot] = (int32_t)i;
-    if (i == 0) flags[4] = (int32_t)n_heavy;
+    if (i == 0) {
+        flags[4] = (int32_t)n_heavy;
+        flags[5] = (int32_t)n_light;
+    }
+}
+
+// Chunks of the split rows: cnt[j] = number of chunks of split row j (0 past the last one) ...
+__global__ void k_split_count(int64_t n, int64_t cap, const int32_t *__restrict__ deg, const int32_t *__restrict__ perm,
+                              const int64_t *__restrict__ hpos, const int64_t *__restrict__ lpos,
+                              int32_t *__restrict__ cnt) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= cap) return;
+    const int64_t first = hpos[n] + lpos[n];
+    cnt[j] = first + j < n ? (deg[perm[first + j]] + kChunk - 1) / kChunk : 0;
+}
+// ... and chunk_srow[c] = j for every chunk c of split row j
+__global__ void k_split_fill(int64_t n, int64_t cap, const int64_t *__restrict__ hpos, const int64_t *__restrict__ lpos,
+                             const int32_t *__restrict__ cnt, const int64_t *__restrict__ chunk_off,
+                             int32_t *__restrict__ chunk_srow) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= cap || hpos[n] + lpos[n] + j >= n) return;
+    for (int k = 0; k < cnt[j]; ++k) chunk_srow[chunk_off[j] + k] = (int32_t)j;
 }
 
 // One wave per row: lane b (0..kColBlocks) finds, by bisection in the sorted row, the offset of the first column
@@ -393,11 +422,24 @@ int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32
 }
 
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
-    k_flag_heavy<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.deg, pb.heavy);
+    int32_t *light = pb.scratch;   // n flags; the canonicalisation is done with this buffer by now
+    k_flag_classes<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.deg, pb.heavy, light);
     GCN_LAUNCH_CHECK();
     int rc = exclusive_scan(n, pb.heavy, pb.hpos, pb.blocksum, st);
     if (rc) return rc;
-    k_place_rows<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.heavy, pb.hpos, pb.perm, pb.flags);
+    rc = exclusive_scan(n, light, pb.lpos, pb.blocksum, st);
+    if (rc) return rc;
+    k_place_rows<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.heavy, light, pb.hpos, pb.lpos, pb.perm,
+                                                                            pb.flags);
+    GCN_LAUNCH_CHECK();
+    k_split_count<<<dim3(blocks_for(pb.split_cap, kThreads)), dim3(kThreads), 0, st>>>(n, pb.split_cap, pb.deg, pb.perm,
+                                                                                        pb.hpos, pb.lpos, pb.split_cnt);
+    GCN_LAUNCH_CHECK();
+    rc = exclusive_scan(pb.split_cap, pb.split_cnt, pb.chunk_off, pb.blocksum, st);
+    if (rc) return rc;
+    k_split_fill<<<dim3(blocks_for(pb.split_cap, kThreads)), dim3(kThreads), 0, st>>>(n, pb.split_cap, pb.hpos, pb.lpos,
+                                                                                       pb.split_cnt, pb.chunk_off,
+                                                                                       pb.chunk_srow);
     GCN_LAUNCH_CHECK();
     const int64_t block = (n + kColBlocks - 1) / kColBlocks;
     k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,

@@ -263,6 +263,76 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
     }
 }
 
+// ------------------------------------------------------------------------------------------------ split rows
+// A row with more than kSplitDegree entries would keep one wave busy long after everything else has ended (a hub of
+// 150,000 entries takes 9,500 dependent steps), so such rows are cut into chunks of kChunk entries: one wave per
+// chunk writes the chunk's plain sum, and k_spmm_chunk_rows adds a row's chunks in ascending order and finishes the row.
+template <typename TIn, int LPR, int U, bool NARROW>
+__global__ __launch_bounds__(kThreads) void k_spmm_chunks(const int64_t *__restrict__ rowptr,
+                                                          const int32_t *__restrict__ col,
+                                                          const int32_t *__restrict__ split_rows,
+                                                          const int64_t *__restrict__ chunk_off,
+                                                          const int32_t *__restrict__ chunk_srow, int64_t n_chunks,
+                                                          int zero_row, const TIn *__restrict__ t, int ld_t, int cols,
+                                                          float *__restrict__ chunk_sums) {
+    constexpr int V = Piece<TIn>::kElems;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = lane / LPR, sub = lane % LPR;
+    const int64_t c = (int64_t)blockIdx.x * (kThreads / 64) + wave;
+    if (c >= n_chunks) return;
+    const int j = chunk_srow[c];
+    const int r = split_rows[j];
+    const int64_t beg = rowptr[r] + (c - chunk_off[j]) * kChunk;
+    const int64_t row_end = rowptr[r + 1];
+    const int64_t end = beg + kChunk < row_end ? beg + kChunk : row_end;
+    const uint32_t lane_bytes = (sub * V < cols) ? sub * 16u : 0u;
+    const uint32_t row_bytes = (uint32_t)ld_t * (uint32_t)sizeof(TIn);
+    float acc0[V], acc1[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc0[i] = acc1[i] = 0.0f;
+    gather_sum<TIn, LPR, U, NARROW>(col, beg, end, zero_row, t, row_bytes, lane_bytes, grp, acc0, acc1);
+    float a[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        a[i] = acc0[i] + acc1[i];
+#pragma unroll
+        for (int d = LPR; d < 64; d <<= 1) a[i] += __shfl_xor(a[i], d, 64);
+    }
+    if (grp == 0 && sub * V < cols) store_elems<V>(chunk_sums + c * cols + sub * V, a);
+}
+
+// One thread per (split row, four columns): the row's chunk sums in ascending order, then the row is finished
+// as the other kernels finish theirs (mode: a SpmmFinish value).
+template <typename TOut>
+__global__ __launch_bounds__(kThreads) void k_spmm_chunk_rows(const int32_t *__restrict__ split_rows,
+                                                              const int64_t *__restrict__ chunk_off, int64_t n_split,
+                                                              const float *__restrict__ chunk_sums, int cols,
+                                                              const float *__restrict__ dinv, TOut *__restrict__ out,
+                                                              int ld_out, Epi ep, int mode) {
+    const int quads = cols / 4;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n_split * quads) return;
+    const int64_t j = i / quads;
+    const int c0 = (int)(i % quads) * 4;
+    const int r = split_rows[j];
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t c = chunk_off[j]; c < chunk_off[j + 1]; ++c) {
+        const float4 q = *reinterpret_cast<const float4 *>(chunk_sums + c * cols + c0);
+        o[0] += q.x;
+        o[1] += q.y;
+        o[2] += q.z;
+        o[3] += q.w;
+    }
+    if (mode == kFinishAddStored) add_stored<4>(out + (int64_t)r * ld_out + c0, o);
+    if (mode != kFinishPlainSum) {
+        const float d = dinv[r];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = finish(o[k] * d, ep, r, c0 + k);
+    }
+    store_elems<4>(out + (int64_t)r * ld_out + c0, o);
+}
+
 // ------------------------------------------------------------------------------------------------ light rows
 template <typename TIn, typename TOut, int LPR, int U, bool NARROW>
 __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restrict__ rowptr,
@@ -369,7 +439,22 @@ int launch(const SpmmArgs &a, hipStream_t st) {
                 a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.finish_mode);
         GCN_LAUNCH_CHECK();
     }
-    const int64_t n_light = a.n - a.n_heavy;
+    if (a.n_split > 0) {
+        const int32_t *split_rows = a.perm + a.n_heavy + a.n_light;
+        const unsigned cgrid = (unsigned)((a.n_chunks + kThreads / 64 - 1) / (kThreads / 64));
+        if (narrow)
+            k_spmm_chunks<TIn, LPR, UW, true><<<dim3(cgrid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, split_rows, a.chunk_off, a.chunk_srow, a.n_chunks, zero_row, t, a.ld_t, a.cols, a.chunk_sums);
+        else
+            k_spmm_chunks<TIn, LPR, UW, false><<<dim3(cgrid), dim3(kThreads), 0, st>>>(
+                a.rowptr, a.col, split_rows, a.chunk_off, a.chunk_srow, a.n_chunks, zero_row, t, a.ld_t, a.cols, a.chunk_sums);
+        GCN_LAUNCH_CHECK();
+        const int64_t items = a.n_split * (a.cols / 4);
+        k_spmm_chunk_rows<TOut><<<dim3((unsigned)((items + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            split_rows, a.chunk_off, a.n_split, a.chunk_sums, a.cols, a.dinv, out, a.ld_out, ep, a.finish_mode);
+        GCN_LAUNCH_CHECK();
+    }
+    const int64_t n_light = a.n_light;
     if (n_light > 0) {
         constexpr int RPB = (kThreads / 64) * (64 / LPR);
         const int nblocks = (int)((n_light + RPB - 1) / RPB);
@@ -397,7 +482,8 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     const int64_t knob = tunable("spmm_phased", -1);
     int W = 0, R = 0;
     if (knob == 0 || !a.segoff || !a.prow || !narrow_ok(a, sizeof(TIn)) || !phased_shape(a.n, &W, &R)) return false;
-    if (knob < 0 && a.n_heavy * 8 < a.n * 7) return false;   // a wave per light row wastes most of its lanes
+    if (knob < 0 && (a.n_heavy + a.n_split) * 8 < a.n * 7) return false;   // a wave per light row wastes most of its lanes
+    if (knob < 0 && a.n_split * 16 > a.n) return false;   // many very long rows: chunks balance better than whole rows
     const int64_t block = (a.n + kColBlocks - 1) / kColBlocks;
     const int64_t row_bytes = (int64_t)a.ld_t * (int64_t)sizeof(TIn);
     if (knob < 0 && ((a.n + 1) * row_bytes <= kL2Bytes || block * row_bytes > kL2Bytes - (512 << 10))) return false;
@@ -457,7 +543,8 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     if (a.n <= 0) return GCN_OK;
     const int v_in = a.t_dtype == GCN_BF16 ? 8 : 4;
     if (a.ld_t % 8 != 0 || a.ld_out % 8 != 0 || a.cols % 8 != 0 || a.cols < 8 || a.cols > a.ld_t || a.cols > a.ld_out ||
-        a.cols > 64 * v_in || a.n_heavy < 0 || a.n_heavy > a.n || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
+        a.cols > 64 * v_in || a.n_heavy < 0 || a.n_light < 0 || a.n_split < 0 || a.n_heavy + a.n_light + a.n_split != a.n ||
+        (a.n_split > 0 && (!a.chunk_sums || !a.chunk_off || !a.chunk_srow || a.n_chunks < a.n_split)) || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
         set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld, types %d -> %d)", a.ld_t, a.ld_out,
                   (long long)a.n_heavy, (long long)a.n, a.t_dtype, a.out_dtype);
         return GCN_EINVAL;

@@ -131,6 +131,30 @@ def test_aggregate_heavy_rows_and_regular_invariant(B, oracle):
     np.testing.assert_allclose(got, sq, rtol=2e-5)
 
 
+@pytest.mark.parametrize("width,bf", [(7, False), (48, False), (128, False), (256, False), (100, True), (300, True)])
+def test_rows_longer_than_the_split_degree_are_summed_in_chunks(B, oracle, width, bf):
+    """Three vertices with about 10,800 neighbours each: cut into chunks of 2,048 entries, one wave per chunk."""
+    wl = workloads.tiny(n=12000)
+    wl.rowptr, wl.col = _heavy_row_workload(n=12000, heavy=(0, 17, 4000))
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    assert np.sort(og.deg)[-3] > 3 * 2048
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(width, 8, wl.n * width).reshape(wl.n, width)
+    got = B.gcn_aggregate(g, torch.from_numpy(x).cuda(), dtype=B.GCN_BF16 if bf else B.GCN_F32).cpu().numpy()
+    H.assert_close(got, oracle.aggregate(og, x), rtol=H.RTOL_BF16 if bf else H.RTOL_F32, what="split rows, width %d" % width)
+    again = B.gcn_aggregate(g, torch.from_numpy(x).cuda(), dtype=B.GCN_BF16 if bf else B.GCN_F32).cpu().numpy()
+    np.testing.assert_array_equal(got, again)
+
+
+def test_full_step_with_split_rows(B, oracle):
+    wl = workloads.tiny(n=12000)
+    wl.rowptr, wl.col = _heavy_row_workload(n=12000, heavy=(0, 17, 4000))
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
 # ------------------------------------------------------------------ the whole step
 def test_tiny_config_full_step(B, oracle):
     wl = workloads.tiny()                              # config 1
