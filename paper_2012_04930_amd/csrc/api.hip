@@ -156,6 +156,8 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
     a.n_light = rc.n_light;
     a.n_split = rc.n_split;
     a.n_chunks = rc.n_chunks;
+    a.xcd_start = pb.xcd_start;
+    a.xcd_rows_max = rc.xcd_rows_max;
     a.chunk_off = pb.chunk_off;
     a.chunk_srow = pb.chunk_srow;
     a.chunk_sums = chunk_sums;
@@ -202,6 +204,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.split_cnt = c.take<int32_t>(g.pb.split_cap);
     g.pb.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
     g.pb.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
+    g.pb.xcd_start = c.take<int32_t>(16);
     g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     int pw = 0, pr = 0;
     const bool phased = phased_shape(n, &pw, &pr);   // (a null pointer says nothing here: a measuring Carver returns null)
@@ -225,6 +228,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.split_cnt = c.take<int32_t>(g.pb.split_cap);
     g.res.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
     g.res.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
+    g.res.xcd_start = c.take<int32_t>(16);
     g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     g.res.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
     g.res.flags = c.take<int32_t>(16);
@@ -424,8 +428,14 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         rc.n_heavy = fl[4];
         rc.n_light = fl[5];
         rc.n_split = n - rc.n_heavy - rc.n_light;
+        int32_t starts[kXcds + 1];
         hipError_t e = hipMemcpyAsync(&rc.n_chunks, pb.chunk_off + pb.split_cap, sizeof(int64_t), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(starts, pb.xcd_start, sizeof(starts), hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
+        rc.xcd_rows_max = 0;
+        if (e == hipSuccess)
+            for (int x = 0; x < kXcds; ++x)
+                if (starts[x + 1] - starts[x] > rc.xcd_rows_max) rc.xcd_rows_max = starts[x + 1] - starts[x];
         return e;
     };
     HIP_OR_FAIL(read_classes(g->pb, flags, g->rows));

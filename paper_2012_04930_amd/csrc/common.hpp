@@ -83,6 +83,9 @@ struct PrepBuffers {
     int64_t *chunk_off;   // split_cap + 1
     int32_t *chunk_srow;  // chunk_cap
     int64_t *lpos;     // n + 1   exclusive prefix of the light flags (scratch)
+    // heavy rows are handed to the XCDs in contiguous runs of about equal numbers of entries (not rows): XCD x takes
+    // the schedule slots xcd_start[x] .. xcd_start[x + 1]
+    int32_t *xcd_start;   // kXcds + 1
     // column blocks: the ids are cut into kColBlocks equal ranges; segoff[r * (kColBlocks + 1) + b] is the offset,
     // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
     int32_t *segoff;   // n * (kColBlocks + 1)
@@ -192,6 +195,8 @@ struct SpmmArgs {
     int64_t n_light;    // rows with a lane group each
     int64_t n_split;    // rows cut into chunks (n_heavy + n_light + n_split = n)
     int64_t n_chunks;
+    const int32_t *xcd_start;   // kXcds + 1 slots: the heavy rows of each XCD
+    int64_t xcd_rows_max;       // the longest of those runs
     const int64_t *chunk_off;
     const int32_t *chunk_srow;
     float *chunk_sums;  // n_chunks x cols floats: the chunks' sums (workspace of the call)

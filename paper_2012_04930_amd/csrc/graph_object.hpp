@@ -8,7 +8,7 @@ struct gcn_graph {
     int64_t n = 0, nnz_in = 0, E = 0, n_train = 0;
     // row classes of the whole pattern and of the residual one: a wave each / a lane group each / cut into chunks
     struct RowClasses {
-        int64_t n_heavy = 0, n_light = 0, n_split = 0, n_chunks = 0;
+        int64_t n_heavy = 0, n_light = 0, n_split = 0, n_chunks = 0, xcd_rows_max = 0;
     } rows, res_rows;
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;

@@ -286,6 +286,32 @@ __global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const
     }
 }
 
+// w[s] = entries of the heavy row in schedule slot s (0 for the other slots)
+__global__ void k_heavy_weights(int64_t n, const int32_t *__restrict__ deg, const int32_t *__restrict__ perm,
+                                const int32_t *__restrict__ flags, int32_t *__restrict__ w) {
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < n) w[s] = s < flags[4] ? deg[perm[s]] : 0;
+}
+// before[s] = entries in the heavy slots before s; xcd_start[x] = first slot with at least x / kXcds of all of them
+__global__ void k_xcd_starts(int64_t n, const int64_t *__restrict__ before, const int32_t *__restrict__ flags,
+                             int32_t *__restrict__ xcd_start) {
+    const int x = threadIdx.x;
+    if (x > kXcds) return;
+    const int64_t n_heavy = flags[4];
+    const int64_t total = before[n];
+    int64_t lo = 0, hi = n_heavy;
+    if (x == kXcds) {
+        lo = n_heavy;
+    } else {
+        const int64_t target = total / kXcds * x + (total % kXcds) * x / kXcds;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (before[mid] < target) lo = mid + 1; else hi = mid;
+        }
+    }
+    xcd_start[x] = (int32_t)lo;
+}
+
 // Chunks of the split rows: cnt[j] = number of chunks of split row j (0 past the last one) ...
 __global__ void k_split_count(int64_t n, int64_t cap, const int32_t *__restrict__ deg, const int32_t *__restrict__ perm,
                               const int64_t *__restrict__ hpos, const int64_t *__restrict__ lpos,
@@ -440,6 +466,13 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     k_split_fill<<<dim3(blocks_for(pb.split_cap, kThreads)), dim3(kThreads), 0, st>>>(n, pb.split_cap, pb.hpos, pb.lpos,
                                                                                        pb.split_cnt, pb.chunk_off,
                                                                                        pb.chunk_srow);
+    GCN_LAUNCH_CHECK();
+    // the heavy rows' shares of the XCDs (pb.heavy and pb.hpos are free again)
+    k_heavy_weights<<<dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, st>>>(n, pb.deg, pb.perm, pb.flags, pb.heavy);
+    GCN_LAUNCH_CHECK();
+    rc = exclusive_scan(n, pb.heavy, pb.hpos, pb.blocksum, st);
+    if (rc) return rc;
+    k_xcd_starts<<<dim3(1), dim3(64), 0, st>>>(n, pb.hpos, pb.flags, pb.xcd_start);
     GCN_LAUNCH_CHECK();
     const int64_t block = (n + kColBlocks - 1) / kColBlocks;
     k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,

@@ -153,10 +153,10 @@ template <typename TIn, typename TOut, int LPR, int U, bool NARROW>
 __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ col,
                                                         const int32_t *__restrict__ perm,
+                                                        const int32_t *__restrict__ xcd_start,
                                                         const float *__restrict__ dinv, int zero_row,
-                                                        int64_t n_rows, const TIn *__restrict__ t, int ld_t,
-                                                        TOut *__restrict__ out, int ld_out, int cols, int nblocks,
-                                                        Epi ep, int mode) {
+                                                        const TIn *__restrict__ t, int ld_t,
+                                                        TOut *__restrict__ out, int ld_out, int cols, Epi ep, int mode) {
     constexpr int V = Piece<TIn>::kElems;
     constexpr int GPW = 64 / LPR;      // lane groups per wave = neighbours per load instruction
     constexpr int STEP = GPW * U;      // neighbours per unrolled step
@@ -165,10 +165,11 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = lane / LPR, sub = lane % LPR;
-    const int blk = xcd_contiguous_block(nblocks);
-    if (blk >= nblocks) return;
-    const int64_t s = (int64_t)blk * RPB + wave;
-    if (s >= n_rows) return;
+    // XCD x (block ids congruent x mod 8) walks its own contiguous run of the schedule; the runs hold about the
+    // same number of entries each, so their lengths in rows differ
+    const int x = blockIdx.x % kXcds;
+    const int64_t s = xcd_start[x] + (int64_t)(blockIdx.x / kXcds) * RPB + wave;
+    if (s >= xcd_start[x + 1]) return;
     const int r = perm[s];
     const int64_t beg = rowptr[r], end = rowptr[r + 1];
     // lanes beyond the row's width re-read its first piece (in bounds, same cache line) and store nothing
@@ -429,14 +430,13 @@ int launch(const SpmmArgs &a, hipStream_t st) {
     TOut *out = static_cast<TOut *>(a.out);
     if (a.n_heavy > 0) {
         constexpr int RPB = kThreads / 64;
-        const int nblocks = (int)((a.n_heavy + RPB - 1) / RPB);
-        const int grid = (nblocks + kXcds - 1) / kXcds * kXcds;
+        const unsigned grid = (unsigned)(kXcds * ((a.xcd_rows_max + RPB - 1) / RPB));
         if (narrow)
             k_spmm_wave<TIn, TOut, LPR, UW, true><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.finish_mode);
+                a.rowptr, a.col, a.perm, a.xcd_start, a.dinv, zero_row, t, a.ld_t, out, a.ld_out, a.cols, ep, a.finish_mode);
         else
             k_spmm_wave<TIn, TOut, LPR, UW, false><<<dim3(grid), dim3(kThreads), 0, st>>>(
-                a.rowptr, a.col, a.perm, a.dinv, zero_row, a.n_heavy, t, a.ld_t, out, a.ld_out, a.cols, nblocks, ep, a.finish_mode);
+                a.rowptr, a.col, a.perm, a.xcd_start, a.dinv, zero_row, t, a.ld_t, out, a.ld_out, a.cols, ep, a.finish_mode);
         GCN_LAUNCH_CHECK();
     }
     if (a.n_split > 0) {
@@ -544,6 +544,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     const int v_in = a.t_dtype == GCN_BF16 ? 8 : 4;
     if (a.ld_t % 8 != 0 || a.ld_out % 8 != 0 || a.cols % 8 != 0 || a.cols < 8 || a.cols > a.ld_t || a.cols > a.ld_out ||
         a.cols > 64 * v_in || a.n_heavy < 0 || a.n_light < 0 || a.n_split < 0 || a.n_heavy + a.n_light + a.n_split != a.n ||
+        (a.n_heavy > 0 && (!a.xcd_start || a.xcd_rows_max < (a.n_heavy + kXcds - 1) / kXcds || a.xcd_rows_max > a.n_heavy)) ||
         (a.n_split > 0 && (!a.chunk_sums || !a.chunk_off || !a.chunk_srow || a.n_chunks < a.n_split)) || (a.t_dtype == GCN_F32 && a.out_dtype != GCN_F32)) {
         set_error("aggregation: unsupported shape (ld %d / %d, heavy %lld of %lld, types %d -> %d)", a.ld_t, a.ld_out,
                   (long long)a.n_heavy, (long long)a.n, a.t_dtype, a.out_dtype);
