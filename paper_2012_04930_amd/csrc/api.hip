@@ -150,6 +150,8 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
     a.dinv = g->pb.dinv;
     a.segoff = pb.segoff;
     a.prow = pb.prow;
+    a.phased_w = (tiles ? g->res_rows : g->rows).phased_w;
+    a.phased_r = (tiles ? g->res_rows : g->rows).phased_r;
     a.n = g->n;
     const gcn_graph::RowClasses &rc = tiles ? g->res_rows : g->rows;
     a.n_heavy = rc.n_heavy;
@@ -206,9 +208,10 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.pb.xcd_start = c.take<int32_t>(16);
     g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
-    int pw = 0, pr = 0;
-    const bool phased = phased_shape(n, &pw, &pr);   // (a null pointer says nothing here: a measuring Carver returns null)
-    g.pb.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
+    const bool phased = phased_possible(n);   // (a null pointer says nothing here: a measuring Carver returns null)
+    const size_t prow_ints = (size_t)kXcds * (kPhasedMaxRows + 8);
+    g.pb.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
+    g.pb.row_start = c.take<int32_t>(16);
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n > g.pb.split_cap ? n : g.pb.split_cap));
     g.pb.flags = c.take<int32_t>(16);
     TileBuffers &tb = g.tiles;
@@ -230,7 +233,8 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.res.xcd_start = c.take<int32_t>(16);
     g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
-    g.res.prow = phased ? c.take<int32_t>((size_t)kXcds * pw * pr) : nullptr;
+    g.res.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
+    g.res.row_start = c.take<int32_t>(16);
     g.res.flags = c.take<int32_t>(16);
     g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
     g.labels = c.take<int32_t>(n);
@@ -406,10 +410,6 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
 
     FAIL_IF(prep_canonical(n, nnz_in, rowptr, col, g->pb, st));
     FAIL_IF(prep_schedule(n, g->pb, st));
-    {
-        int pw = 0, pr = 0;
-        if (g->pb.prow && phased_shape(n, &pw, &pr)) FAIL_IF(prep_balance_rows(n, g->pb.deg, pw, pr, g->pb.prow, st));
-    }
     const size_t x_es = store_dtype == GCN_BF16 ? 2 : 4;
     FAIL_IF(pad_rows(feat, n, f, g->x, store_dtype, g->ldf, nullptr, st));
     FAIL_IF(fill_zero((char *)g->x + (size_t)n * g->ldf * x_es, (size_t)g->ldf * x_es, st));
@@ -436,6 +436,23 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         if (e == hipSuccess)
             for (int x = 0; x < kXcds; ++x)
                 if (starts[x + 1] - starts[x] > rc.xcd_rows_max) rc.xcd_rows_max = starts[x + 1] - starts[x];
+        // the phased schedule: equal entries per XCD; available when the longest of its row ranges fits
+        rc.phased_w = rc.phased_r = 0;
+        if (e == hipSuccess && pb.prow) {
+            e = hipMemcpyAsync(starts, pb.row_start, sizeof(starts), hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipStreamSynchronize(st);
+            int64_t longest = 0;
+            if (e == hipSuccess)
+                for (int x = 0; x < kXcds; ++x)
+                    if (starts[x + 1] - starts[x] > longest) longest = starts[x + 1] - starts[x];
+            int w = 0, r = 0;
+            if (e == hipSuccess && phased_shape(longest, &w, &r)) {
+                if (prep_balance_rows(n, pb.deg, pb.row_start, w, r, pb.prow, st) == GCN_OK) {
+                    rc.phased_w = w;
+                    rc.phased_r = r;
+                }
+            }
+        }
         return e;
     };
     HIP_OR_FAIL(read_classes(g->pb, flags, g->rows));
@@ -464,9 +481,6 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
             FAIL_IF(tiles_build(n, g->pb.rowptr, g->pb.col, g->n_tiles, g->tiles, g->res, st));
             FAIL_IF(fill_zero(g->res.flags, 16 * sizeof(int32_t), st));
             FAIL_IF(prep_schedule(n, g->res, st));
-            int pw = 0, pr = 0;
-            if (g->res.prow && phased_shape(n, &pw, &pr))
-                FAIL_IF(prep_balance_rows(n, g->res.deg, pw, pr, g->res.prow, st));
             HIP_OR_FAIL(hipMemcpyAsync(flags, g->res.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
             HIP_OR_FAIL(hipStreamSynchronize(st));
             HIP_OR_FAIL(read_classes(g->res, flags, g->res_rows));

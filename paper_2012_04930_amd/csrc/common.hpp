@@ -86,6 +86,7 @@ struct PrepBuffers {
     // heavy rows are handed to the XCDs in contiguous runs of about equal numbers of entries (not rows): XCD x takes
     // the schedule slots xcd_start[x] .. xcd_start[x + 1]
     int32_t *xcd_start;   // kXcds + 1
+    int32_t *row_start;   // kXcds + 1: contiguous id ranges with equal numbers of entries (phased schedule)
     // column blocks: the ids are cut into kColBlocks equal ranges; segoff[r * (kColBlocks + 1) + b] is the offset,
     // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
     int32_t *segoff;   // n * (kColBlocks + 1)
@@ -104,18 +105,21 @@ int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_
 int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, PrepBuffers &pb,
                    hipStream_t st);
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
-// Phased aggregation schedule: each XCD owns the rows of one of kXcds equal id ranges, each of its W waves R rows.
-// false when the graph is too large for it: more than 8 rows per wave with 896 waves per XCD (32 CUs x 4 SIMDs x
-// 7 waves, what the kernel's register use lets be resident at once; the schedule wants the whole grid resident).
-inline bool phased_shape(int64_t n, int *W, int *R) {
-    const int64_t block = (n + kXcds - 1) / kXcds;
-    const int64_t need = (block + 895) / 896;
-    if (need > 8) return false;
+// Phased aggregation schedule: XCD x owns the rows row_start[x] .. row_start[x + 1] (contiguous id ranges holding
+// equal numbers of entries), each of its W waves R of them.  Not available when an XCD would own more than
+// kPhasedMaxRows rows: 8 rows per wave with 896 waves per XCD (32 CUs x 4 SIMDs x 7 waves, what the kernel's
+// register use lets be resident at once; the schedule likes the whole grid resident).
+constexpr int kPhasedMaxRows = 8 * 896;
+inline bool phased_possible(int64_t n) { return n <= (int64_t)kXcds * kPhasedMaxRows; }   // decides the allocation
+inline bool phased_shape(int64_t max_rows_per_xcd, int *W, int *R) {
+    const int64_t need = (max_rows_per_xcd + 895) / 896;
+    if (max_rows_per_xcd < 1 || need > 8) return false;
     *R = need <= 4 ? 4 : (need <= 6 ? 6 : 8);
-    *W = (int)((block + *R - 1) / *R);
+    *W = (int)((max_rows_per_xcd + *R - 1) / *R);
     return true;
 }
-int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st);
+int prep_balance_rows(int64_t n, const int32_t *deg, const int32_t *row_start, int W, int R, int32_t *prow,
+                      hipStream_t st);
 // ---------------------------------------------------------------------------------------------
 // Dense 32 x 32 tiles of the adjacency pattern (tiles.hip)
 struct TileBuffers {
@@ -190,6 +194,7 @@ struct SpmmArgs {
     const float *dinv;
     const int32_t *segoff;  // column-block offsets per row (see PrepBuffers)
     const int32_t *prow;    // rows per wave of the phased schedule, or null
+    int phased_w, phased_r; // waves per XCD and rows per wave of that schedule (0: not available)
     int64_t n;
     int64_t n_heavy;    // rows with a wave each
     int64_t n_light;    // rows with a lane group each

@@ -9,6 +9,7 @@ struct gcn_graph {
     // row classes of the whole pattern and of the residual one: a wave each / a lane group each / cut into chunks
     struct RowClasses {
         int64_t n_heavy = 0, n_light = 0, n_split = 0, n_chunks = 0, xcd_rows_max = 0;
+        int phased_w = 0, phased_r = 0;   // 0: no phased schedule for this pattern
     } rows, res_rows;
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;

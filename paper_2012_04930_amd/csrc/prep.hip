@@ -286,6 +286,28 @@ __global__ void k_place_rows(int64_t n, const int32_t *__restrict__ heavy, const
     }
 }
 
+// row_start[x] = first row with at least x / kXcds of all entries before it (rowptr is that prefix sum)
+__global__ void k_row_starts(int64_t n, const int64_t *__restrict__ rowptr, int32_t *__restrict__ row_start,
+                             int by_entries) {
+    const int x = threadIdx.x;
+    if (x > kXcds) return;
+    const int64_t total = rowptr[n];
+    int64_t lo = 0, hi = n;
+    if (x == kXcds) {
+        lo = n;
+    } else if (!by_entries) {
+        const int64_t block = (n + kXcds - 1) / kXcds;
+        lo = block * x < n ? block * x : n;
+    } else {
+        const int64_t target = total / kXcds * x + (total % kXcds) * x / kXcds;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (rowptr[mid] < target) lo = mid + 1; else hi = mid;
+        }
+    }
+    row_start[x] = (int32_t)lo;
+}
+
 // w[s] = entries of the heavy row in schedule slot s (0 for the other slots)
 __global__ void k_heavy_weights(int64_t n, const int32_t *__restrict__ deg, const int32_t *__restrict__ perm,
                                 const int32_t *__restrict__ flags, int32_t *__restrict__ w) {
@@ -356,12 +378,13 @@ __global__ __launch_bounds__(kThreads) void k_segment_offsets(int64_t n, const i
 // degree (descending, ties by id) in LDS, then deals them to W waves in serpentine order, R per wave, so that every
 // wave carries nearly the same number of entries: prow[(x * W + q) * R + j] = row (or -1).
 constexpr int kMaxRangeRows = 8192;
-__global__ __launch_bounds__(kThreads) void k_balance_rows(int64_t n, int64_t block, const int32_t *__restrict__ deg,
-                                                           int W, int R, int32_t *__restrict__ prow) {
+__global__ __launch_bounds__(kThreads) void k_balance_rows(int64_t n, const int32_t *__restrict__ row_start,
+                                                           const int32_t *__restrict__ deg, int W, int R,
+                                                           int32_t *__restrict__ prow) {
     __shared__ unsigned long long key[kMaxRangeRows];
     const int x = blockIdx.x;
-    const int64_t lo = (int64_t)x * block;
-    const int64_t hi = lo + block < n ? lo + block : n;
+    const int64_t lo = row_start[x];
+    const int64_t hi = row_start[x + 1] < n ? row_start[x + 1] : n;
     const int m = hi > lo ? (int)(hi - lo) : 0;
     int P = 2;
     while (P < m) P <<= 1;
@@ -474,6 +497,8 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     if (rc) return rc;
     k_xcd_starts<<<dim3(1), dim3(64), 0, st>>>(n, pb.hpos, pb.flags, pb.xcd_start);
     GCN_LAUNCH_CHECK();
+    k_row_starts<<<dim3(1), dim3(64), 0, st>>>(n, pb.rowptr, pb.row_start, (int)tunable("phased_balance", 1));
+    GCN_LAUNCH_CHECK();
     const int64_t block = (n + kColBlocks - 1) / kColBlocks;
     k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,
                                                                                       pb.segoff);
@@ -481,13 +506,13 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     return GCN_OK;
 }
 
-int prep_balance_rows(int64_t n, const int32_t *deg, int W, int R, int32_t *prow, hipStream_t st) {
-    const int64_t block = (n + kXcds - 1) / kXcds;
-    if (block > kMaxRangeRows) {
+int prep_balance_rows(int64_t n, const int32_t *deg, const int32_t *row_start, int W, int R, int32_t *prow,
+                      hipStream_t st) {
+    if ((int64_t)W * R > kMaxRangeRows) {
         set_error("phased schedule: more than %d rows per range", kMaxRangeRows);
         return GCN_EINVAL;
     }
-    k_balance_rows<<<dim3(kXcds), dim3(kThreads), 0, st>>>(n, block, deg, W, R, prow);
+    k_balance_rows<<<dim3(kXcds), dim3(kThreads), 0, st>>>(n, row_start, deg, W, R, prow);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

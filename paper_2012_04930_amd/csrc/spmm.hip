@@ -480,8 +480,8 @@ constexpr int64_t kL2Bytes = 4 << 20;
 template <typename TIn, typename TOut, int LPR, int U>
 bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     const int64_t knob = tunable("spmm_phased", -1);
-    int W = 0, R = 0;
-    if (knob == 0 || !a.segoff || !a.prow || !narrow_ok(a, sizeof(TIn)) || !phased_shape(a.n, &W, &R)) return false;
+    const int W = a.phased_w, R = a.phased_r;
+    if (knob == 0 || !a.segoff || !a.prow || W < 1 || !narrow_ok(a, sizeof(TIn))) return false;
     if (knob < 0 && (a.n_heavy + a.n_split) * 8 < a.n * 7) return false;   // a wave per light row wastes most of its lanes
     if (knob < 0 && a.n_split * 16 > a.n) return false;   // many very long rows: chunks balance better than whole rows
     const int64_t block = (a.n + kColBlocks - 1) / kColBlocks;
