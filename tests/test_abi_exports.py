@@ -34,3 +34,32 @@ def test_argument_errors_need_no_gpu():
     assert L.gcn_forward(None, 1, None) == -1
     assert L.gcn_backward(None, None) == -1
     assert L.gcn_sgd_step(None, 0.1, None) == -1
+
+
+def test_null_handles_and_sizes_of_the_later_entry_points_need_no_gpu():
+    from paper_2012_04930_amd import binding
+    L = binding.lib()
+    need = ctypes.c_size_t()
+    assert need.value == 0
+    # workspace sizes grow with the input and stay multiples of the 256-byte alignment the library asks for
+    sizes = []
+    for nnz in (0, 10_000, 1_000_000):
+        assert L.gcn_graph_workspace_bytes(5000, nnz, 100, 0, ctypes.byref(need)) == 0
+        assert need.value % 256 == 0
+        sizes.append(need.value)
+    assert sizes[0] < sizes[1] < sizes[2]
+    assert L.gcn_graph_workspace_bytes(5000, 10_000, 100, 1, ctypes.byref(need)) == 0 and need.value < sizes[1]   # bfloat16 X
+    assert L.gcn_augment_workspace_bytes(0, ctypes.byref(need)) == -1
+    assert L.gcn_augment_workspace_bytes(1000, ctypes.byref(need)) == 0 and need.value > 0
+    for call in (lambda: L.gcn_graph_tile_info(None, None, None, None),
+                 lambda: L.gcn_graph_get_tiles(None, None, None, None, None, None, None, None),
+                 lambda: L.gcn_sage_workspace_bytes(None, 128, 25, 10, 256, ctypes.byref(need)),
+                 lambda: L.gcn_sage_forward(None, None, 1, 0, None),
+                 lambda: L.gcn_sage_loss_acc(None, None, None, None, None),
+                 lambda: L.gcn_sage_backward(None, None),
+                 lambda: L.gcn_sage_adam_step(None, 1e-4, 0.9, 0.999, 1e-8, None),
+                 lambda: L.gcn_adam_step(None, 0.02, 0.9, 0.999, 1e-8, None),
+                 lambda: L.gcn_model_workspace_bytes(None, 2, None, 0, ctypes.byref(need))):
+        assert call() == -1
+        assert len(L.gcn_last_error()) > 0
+    assert L.gcn_set_tunable(b"spmm_tiles", -1) == 0
