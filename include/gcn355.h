@@ -239,8 +239,17 @@ int gcn_timing_reset(void);
 int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
 
 /* Benchmark sweeps: sets a named integer knob that selects among equivalent kernel variants or launch
- * shapes (e.g. "spmm_variant").  Results do not depend on any knob beyond rounding order.  Unknown names
- * are stored and ignored. */
+ * shapes.  Results do not depend on any knob beyond rounding order.  Unknown names are stored and ignored.
+ *   "cache_ax"          0 / 1 / 2    layer 1 as (A_hat X) W_1 from a cached A_hat X: never / when d_0 <= d_1 (default) /
+ *                                    always; read by gcn_model_create
+ *   "spmm_tiles"        -1 / 0 / 1   dense tiles: when they hold a quarter of the entries (default) / never / whenever
+ *                                    there is one; read by gcn_graph_create, 0 also per call
+ *   "tile_min_entries"  64..1024     entries that make a 32 x 32 tile dense (default 128); read by gcn_graph_create
+ *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
+ *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows
+ *   "phased_balance"    1 / 0        XCD row ranges of the phased schedule by entries (default) / by rows; read by
+ *                                    gcn_graph_create
+ *   "spmm_u"            4 / 8 / 16   gathers in flight per lane group at 17..32 sixteen-byte pieces per row (default 8) */
 int gcn_set_tunable(const char *name, int64_t value);
 
 /* Measurement aid: launches n_blocks workgroups of 256 threads and writes, for each, the id of the XCD it ran on
