@@ -192,17 +192,18 @@ __global__ __launch_bounds__(kThreads) void k_spmm_wave(const int64_t *__restric
 
 // ------------------------------------------------------------------------------------------------ phased schedule
 // For inputs a few times larger than one L2 (one partition of a distributed graph is that size): the vertex ids
-// are cut into kXcds equal row ranges and each of those into kRangesPerXcd column ranges.  XCD x owns the rows of
-// row range x; each of its waves owns R rows for the whole kernel and keeps their sums in registers.  The work
-// goes in kColBlocks phases: in phase s every wave of XCD x adds, for each of its rows, the entries whose columns
-// lie in column range (kRangesPerXcd (x + 1) + s) mod kColBlocks, so the XCDs are always kRangesPerXcd ranges apart
-// and each ends on its own rows' ranges (rows are sorted, so a range is one contiguous segment, found through segoff).  All waves start together and
-// carry similar loads (rows are dealt to waves by degree, in serpentine order), so for a while an XCD's gathers
-// fall into one range (about 3 MB of the input), which its L2 holds: most entries outside a row's own
+// are cut into kXcds equal row ranges and kColBlocks equal column ranges.  XCD x owns the rows of row range x; each
+// of its waves owns R rows for the whole kernel and keeps their sums in registers.  The work goes in kColBlocks / G
+// phases of G adjacent column ranges: in a phase every wave of XCD x adds, for each of its rows, the entries whose
+// columns lie in the phase's ranges (rows are sorted, so that is one contiguous segment, found through segoff).
+// The XCDs start on different ranges, each right behind the ranges of its own rows and ending on them: those hold
+// the rows' neighbourhood, the long pass, and right after the common start, on the short ones, all waves still
+// move in step.  Waves carry similar loads (rows are dealt to waves by degree, in serpentine order), so for a
+// while an XCD's gathers fall into one phase's ranges, which its L2 holds: most entries outside a row's own
 // neighbourhood stop missing.  There is no synchronisation of any kind: a row never leaves its wave, and waves
 // that drift apart only lose hits.  (Measured on the benchmark partition: L2 misses -54 %, time -8 %; pacing the
 // waves with counters between phases removed 86 % of the misses but cost more time in waiting than it saved.)
-template <typename TIn, typename TOut, int LPR, int U, int R>
+template <typename TIn, typename TOut, int LPR, int U, int R, int G>
 __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restrict__ rowptr,
                                                           const int32_t *__restrict__ col,
                                                           const int32_t *__restrict__ segoff,
@@ -229,20 +230,20 @@ __global__ __launch_bounds__(kThreads) void k_spmm_phased(const int64_t *__restr
     for (int j = 0; j < R; ++j)
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[j][i] = 0.0f;
-    // the ranges other than the wave's own come first: they are short, and right after the common start all
-    // waves still move in step; the long pass over the own range (its rows' neighbourhood) ends the kernel
-    for (int s = 0; s < kColBlocks; ++s) {
-        const int b = (kRangesPerXcd * (x + 1) + s) % kColBlocks;
+    constexpr int kPhases = kColBlocks / G;
+    const int own = kRangesPerXcd * x / G;   // the phase that holds the column ranges of this XCD's rows: the last one
+    for (int s = 1; s <= kPhases; ++s) {
+        const int b = (own + s) % kPhases * G;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const int64_t r = rows[j];
             if (r >= 0) {
                 const int64_t row_beg = rowptr[r];
-                const int32_t *so = segoff + r * (kColBlocks + 1) + b;
+                const int32_t *so = segoff + r * (kColBlocks + 1);
                 float a1[V];
 #pragma unroll
                 for (int i = 0; i < V; ++i) a1[i] = 0.0f;
-                gather_sum<TIn, LPR, U, true>(col, row_beg + so[0], row_beg + so[1], zero_row, t, row_bytes, lane_bytes,
+                gather_sum<TIn, LPR, U, true>(col, row_beg + so[b], row_beg + so[b + G], zero_row, t, row_bytes, lane_bytes,
                                               grp, acc[j], a1);
                 addv(acc[j], a1);
             }
@@ -473,9 +474,12 @@ int launch(const SpmmArgs &a, hipStream_t st) {
 }
 
 // The phased schedule applies when nearly every row is heavy, the input is larger than one L2 but one column range of it
-// (an eighth) fits, and a wave gets at most 8 rows with the whole grid resident.  Knob "spmm_phased": -1 automatic
+// fits, and a wave gets at most 8 rows with the whole grid resident.  Knob "spmm_phased": -1 automatic
 // (default), 0 never, 1 whenever the shape allows.
 constexpr int64_t kL2Bytes = 4 << 20;
+// A phase's input rows may take 5/4 of one L2: on the benchmark partition width 128 is fastest at 3.0 MB per phase
+// (1.5 MB: +19 %, 6.1 MB: +14 %) and width 48 at 4.6 MB (2.3 MB: +6 %, 9.1 MB: +5 %).
+constexpr int64_t kPhaseBytes = 5 << 20;
 
 template <typename TIn, typename TOut, int LPR, int U>
 bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
@@ -492,13 +496,26 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     const TIn *t = static_cast<const TIn *>(a.t);
     TOut *out = static_cast<TOut *>(a.out);
     const int zero_row = (int)a.n;
-#define GCN_PHASED(RR)                                                                                               \
-    k_spmm_phased<TIn, TOut, LPR, U, RR><<<dim3(grid), dim3(kThreads), 0, st>>>(                                      \
+    // column ranges per phase (1, 2, 4 or 8): the most whose rows take at most kPhaseBytes.  Knob "phased_group":
+    // 0 = this rule.
+    int64_t group = tunable("phased_group", 0);
+    if (group <= 0)
+        for (group = kColBlocks / 2; group > 1 && group * block * row_bytes > kPhaseBytes;) group /= 2;
+#define GCN_PHASED(RR, GG)                                                                                           \
+    k_spmm_phased<TIn, TOut, LPR, U, RR, GG><<<dim3(grid), dim3(kThreads), 0, st>>>(                                  \
         a.rowptr, a.col, a.segoff, a.prow, W, a.dinv, zero_row, a.n, block, t, a.ld_t, out, a.ld_out, \
         a.cols, ep, a.finish_mode)
-    if (R == 4) GCN_PHASED(4);
-    else if (R == 6) GCN_PHASED(6);
-    else GCN_PHASED(8);
+#define GCN_PHASED_R(GG)                                                                                             \
+    do {                                                                                                             \
+        if (R == 4) GCN_PHASED(4, GG);                                                                               \
+        else if (R == 6) GCN_PHASED(6, GG);                                                                          \
+        else GCN_PHASED(8, GG);                                                                                      \
+    } while (0)
+    if (group >= 8) GCN_PHASED_R(8);
+    else if (group >= 4) GCN_PHASED_R(4);
+    else if (group >= 2) GCN_PHASED_R(2);
+    else GCN_PHASED_R(1);
+#undef GCN_PHASED_R
 #undef GCN_PHASED
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -521,10 +538,8 @@ int launch_by_width(const SpmmArgs &a, hipStream_t st) {
     const int pieces = (a.cols + Piece<TIn>::kElems - 1) / Piece<TIn>::kElems;   // 16-byte pieces per row
     int rc = GCN_OK;
     if (pieces > 16 && pieces <= 32 && try_phased<TIn, TOut, 32, 4>(a, st, &rc)) return rc;
-    if (tunable("spmm_phased", -1) > 0) {   // narrower rows: the short segments cost more than the hits gain
-        if (pieces > 4 && pieces <= 8 && try_phased<TIn, TOut, 8, 2>(a, st, &rc)) return rc;
-        if (pieces > 8 && pieces <= 16 && try_phased<TIn, TOut, 16, 2>(a, st, &rc)) return rc;
-    }
+    if (pieces > 4 && pieces <= 8 && try_phased<TIn, TOut, 8, 2>(a, st, &rc)) return rc;
+    if (pieces > 8 && pieces <= 16 && try_phased<TIn, TOut, 16, 2>(a, st, &rc)) return rc;
     if (pieces <= 4) return launch<TIn, TOut, 4, 2, 4>(a, st);
     if (pieces <= 8) return launch<TIn, TOut, 8, 2, 8>(a, st);
     if (pieces <= 16) return launch<TIn, TOut, 16, 4, 8>(a, st);

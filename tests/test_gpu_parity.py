@@ -439,6 +439,25 @@ def test_phased_schedule_matches_oracle_and_the_plain_schedule(B, oracle, width,
     np.testing.assert_allclose(out[1], out[0], rtol=0, atol=3e-6 * np.abs(ref).max() * (300 if bf else 1))
 
 
+@pytest.mark.parametrize("width", [41, 128])
+def test_phased_schedule_with_every_number_of_column_ranges_per_phase(B, oracle, width):
+    """A phase may take 1, 2, 4 or 8 adjacent column ranges: every entry is still added exactly once."""
+    wl = workloads.reddit_partition(scale=0.1)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    g = H.gpu_graph(B, wl)
+    x = rng.normal_f32(width, 5, wl.n * width).reshape(wl.n, width)
+    xd = torch.from_numpy(x).cuda()
+    ref = oracle.aggregate(og, x)
+    B.gcn_set_tunable("spmm_phased", 1)
+    try:
+        for group in (1, 2, 4, 8, 0):
+            B.gcn_set_tunable("phased_group", group)
+            H.assert_close(B.gcn_aggregate(g, xd).cpu().numpy(), ref, rtol=H.RTOL_F32, what="group %d" % group)
+    finally:
+        B.gcn_set_tunable("spmm_phased", -1)
+        B.gcn_set_tunable("phased_group", 0)
+
+
 def test_workgroups_are_dealt_round_robin_over_the_xcds(B):
     """The aggregation kernels give the workgroups b with equal b mod 8 one contiguous range of rows and count on them
     sharing an XCD (and its L2).  That rests on this dispatch order: workgroup b runs on XCD (b + s) mod 8, with a
