@@ -249,6 +249,8 @@ int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
  *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows
  *   "phased_balance"    1 / 0        XCD row ranges of the phased schedule by entries (default) / by rows; read by
  *                                    gcn_graph_create
+ *   "phased_group"      0 / 1,2,4,8  column ranges (sixteenths of the ids) per phase of the phased schedule: as many as
+ *                                    5 MB of input rows allow (default) / that many
  *   "spmm_u"            4 / 8 / 16   gathers in flight per lane group at 17..32 sixteen-byte pieces per row (default 8) */
 int gcn_set_tunable(const char *name, int64_t value);
 
