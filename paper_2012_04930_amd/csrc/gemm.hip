@@ -270,11 +270,20 @@ template <int MODE>
 int launch_rows(GemmArgs &g, hipStream_t st) {   // nn, nt
     if (g.N > 64) {
         const int ntiles = (g.N + 127) / 128;
-        const unsigned grid = (unsigned)((g.M + 63) / 64) * ntiles;
-        k_gemm<MODE, 2, 2, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
+        const int64_t tiles64 = (g.M + 63) / 64 * ntiles;
+        if (tiles64 < 4 * 256) {
+            // fewer than four workgroups per CU: half-height tiles double the waves that hide each other's waits
+            const unsigned grid = (unsigned)((g.M + 31) / 32) * ntiles;
+            k_gemm<MODE, 1, 4, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
+        } else {
+            k_gemm<MODE, 2, 2, 2><<<dim3((unsigned)tiles64), dim3(kThreads), 0, st>>>(g);
+        }
     } else if (g.N > 32) {
         const unsigned grid = (unsigned)((g.M + 127) / 128);
-        k_gemm<MODE, 4, 1, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
+        if (grid < 4 * 256)   // as above
+            k_gemm<MODE, 2, 2, 1><<<dim3((unsigned)((g.M + 63) / 64)), dim3(kThreads), 0, st>>>(g);
+        else
+            k_gemm<MODE, 4, 1, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
     } else {
         const unsigned grid = (unsigned)((g.M + 127) / 128);
         k_gemm<MODE, 4, 1, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
