@@ -271,8 +271,9 @@ int launch_rows(GemmArgs &g, hipStream_t st) {   // nn, nt
     if (g.N > 64) {
         const int ntiles = (g.N + 127) / 128;
         const int64_t tiles64 = (g.M + 63) / 64 * ntiles;
-        if (tiles64 < 4 * 256) {
+        if (tiles64 < 4 * 256 && g.K <= 128) {
             // fewer than four workgroups per CU: half-height tiles double the waves that hide each other's waits
+            // (over a long shared dimension the second read of B costs as much as that gains)
             const unsigned grid = (unsigned)((g.M + 31) / 32) * ntiles;
             k_gemm<MODE, 1, 4, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(g);
         } else {
