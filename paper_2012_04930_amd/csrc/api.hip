@@ -207,8 +207,8 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
     g.pb.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.pb.xcd_start = c.take<int32_t>(16);
-    g.pb.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
     const bool phased = phased_possible(n);   // (a null pointer says nothing here: a measuring Carver returns null)
+    g.pb.segoff = phased ? c.take<int32_t>((size_t)n * (kColBlocks + 1)) : nullptr;
     const size_t prow_ints = (size_t)kXcds * (kPhasedMaxRows + 8);
     g.pb.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
     g.pb.row_start = c.take<int32_t>(16);
@@ -232,7 +232,7 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
     g.res.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
     g.res.xcd_start = c.take<int32_t>(16);
-    g.res.segoff = c.take<int32_t>((size_t)n * (kColBlocks + 1));
+    g.res.segoff = phased ? c.take<int32_t>((size_t)n * (kColBlocks + 1)) : nullptr;
     g.res.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
     g.res.row_start = c.take<int32_t>(16);
     g.res.flags = c.take<int32_t>(16);

@@ -89,7 +89,7 @@ struct PrepBuffers {
     int32_t *row_start;   // kXcds + 1: contiguous id ranges with equal numbers of entries (phased schedule)
     // column blocks: the ids are cut into kColBlocks equal ranges; segoff[r * (kColBlocks + 1) + b] is the offset,
     // from the start of row r, of its first column in range b (and the row length for b = kColBlocks)
-    int32_t *segoff;   // n * (kColBlocks + 1)
+    int32_t *segoff;   // n * (kColBlocks + 1); null for graphs too large for the phased schedule
     // phased schedule (only for graphs small enough for it, else unused): rows of each wave, see phased_shape()
     int32_t *prow;     // kXcds * W * R
     // scratch

@@ -499,10 +499,12 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     GCN_LAUNCH_CHECK();
     k_row_starts<<<dim3(1), dim3(64), 0, st>>>(n, pb.rowptr, pb.row_start, (int)tunable("phased_balance", 1));
     GCN_LAUNCH_CHECK();
-    const int64_t block = (n + kColBlocks - 1) / kColBlocks;
-    k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,
-                                                                                      pb.segoff);
-    GCN_LAUNCH_CHECK();
+    if (pb.segoff) {   // only graphs small enough for the phased schedule carry the table
+        const int64_t block = (n + kColBlocks - 1) / kColBlocks;
+        k_segment_offsets<<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, pb.rowptr, pb.col, block,
+                                                                                          pb.segoff);
+        GCN_LAUNCH_CHECK();
+    }
     return GCN_OK;
 }
 
