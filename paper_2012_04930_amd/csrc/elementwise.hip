@@ -128,6 +128,96 @@ __global__ __launch_bounds__(kThreads) void k_loss(int64_t n, int classes, const
     }
 }
 
+// The same for at most 64 classes: a group of 16 lanes per vertex (four vertices per wave at a time), each lane
+// holding up to four logits in registers, so a vertex costs one pass over its row and two 4-step reductions.
+template <typename TDz>
+__global__ __launch_bounds__(kThreads) void k_loss_small(int64_t n, int classes, const float *__restrict__ logits,
+                                                         int ld, const int32_t *__restrict__ labels,
+                                                         const uint8_t *__restrict__ mask,
+                                                         const float *__restrict__ dinv, float inv_ntrain,
+                                                         TDz *__restrict__ dzs, int ld_dz,
+                                                         double *__restrict__ loss_part,
+                                                         long long *__restrict__ corr_part) {
+    constexpr int kLanes = 16, kPerLane = 4;
+    __shared__ double s_loss[kThreads / 64];
+    __shared__ long long s_corr[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % kLanes, grp = lane / kLanes;
+    const int64_t groups_total = (int64_t)gridDim.x * (kThreads / kLanes);
+    double my_loss = 0.0;
+    long long my_corr = 0;
+    for (int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * (64 / kLanes) + grp; v < n; v += groups_total) {
+        const float *z = logits + v * ld;
+        TDz *g = dzs + v * ld_dz;
+        if (!mask[v]) {
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i)
+                if (sub + kLanes * i < classes) g[sub + kLanes * i] = narrow<TDz>(0.0f);
+            continue;
+        }
+        float x[kPerLane];
+        float m = -INFINITY;
+        int arg = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int c = sub + kLanes * i;
+            x[i] = c < classes ? z[c] : -INFINITY;
+            if (x[i] > m) {   // ascending c: the lowest index of the maximum
+                m = x[i];
+                arg = c;
+            }
+        }
+#pragma unroll
+        for (int d = kLanes / 2; d > 0; d >>= 1) {
+            const float om = __shfl_xor(m, d, 64);
+            const int oa = __shfl_xor(arg, d, 64);
+            if (om > m || (om == m && oa < arg)) {
+                m = om;
+                arg = oa;
+            }
+        }
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i)
+            if (sub + kLanes * i < classes) s += expf(x[i] - m);
+#pragma unroll
+        for (int d = kLanes / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, 64);
+        const float lse = m + logf(s);
+        const int y = labels[v];
+        const float scale = dinv[v] * inv_ntrain;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int c = sub + kLanes * i;
+            if (c < classes) g[c] = narrow<TDz>((expf(x[i] - lse) - (c == y ? 1.0f : 0.0f)) * scale);
+        }
+        if (sub == 0) {
+            my_loss += (double)(lse - z[y]);
+            my_corr += (arg == y) ? 1 : 0;
+        }
+    }
+    // the four group leaders of the wave, in a fixed order
+#pragma unroll
+    for (int d = kLanes; d < 64; d <<= 1) {
+        my_loss += __shfl_xor(my_loss, d, 64);
+        my_corr += __shfl_xor(my_corr, d, 64);
+    }
+    if (lane == 0) {
+        s_loss[wave] = my_loss;
+        s_corr[wave] = my_corr;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0;
+        long long c = 0;
+        for (int w = 0; w < kThreads / 64; ++w) {
+            a += s_loss[w];
+            c += s_corr[w];
+        }
+        loss_part[blockIdx.x] = a;
+        corr_part[blockIdx.x] = c;
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void k_loss_final(int parts, const double *__restrict__ loss_part,
                                                          const long long *__restrict__ corr_part, double inv_ntrain,
                                                          float *__restrict__ result,
@@ -275,11 +365,17 @@ int fill_zero(void *p, size_t bytes, hipStream_t st) {
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
                  const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
                  long long *corr_part, float *result, long long *result_correct, hipStream_t st) {
-    int blocks = (int)((n + 3) / 4);
+    int blocks = (int)(classes <= 64 ? (n + 15) / 16 : (n + 3) / 4);
     if (blocks > kLossBlocks) blocks = kLossBlocks;
     if (blocks < 1) blocks = 1;
     const float inv = (float)(1.0 / (double)n_train);
-    if (dz_dtype == GCN_BF16)
+    if (classes <= 64 && dz_dtype == GCN_BF16)
+        k_loss_small<bf16_t><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
+                                                                      (bf16_t *)dzs, ld_dz, loss_part, corr_part);
+    else if (classes <= 64)
+        k_loss_small<float><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
+                                                                     (float *)dzs, ld_dz, loss_part, corr_part);
+    else if (dz_dtype == GCN_BF16)
         k_loss<bf16_t><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
                                                                 (bf16_t *)dzs, ld_dz, loss_part, corr_part);
     else

@@ -214,34 +214,56 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
     }
 }
 
-// c[i] = sum over splits, ascending, of partials[split][i]; one float4 per thread, loads issued eight
-// splits ahead of the (ordered) additions
-__global__ void k_reduce_partials(const float4 *__restrict__ partials, int splits, size_t count4,
-                                  float4 *__restrict__ c) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count4) return;
+// c[i] = sum over the splits of partials[split][i], in a fixed order: the splits are cut into kReduceGroups
+// consecutive runs, eight threads add one run each in ascending order (one float4 of the output per thread, four
+// loads in flight), and the runs' sums are added in ascending order.  A single thread per output would wait
+// through a hundred dependent round trips.
+constexpr int kReduceGroups = 8;
+constexpr int kReduceOutputs = 256 / kReduceGroups;   // float4 outputs per workgroup
+
+__global__ __launch_bounds__(256) void k_reduce_partials(const float4 *__restrict__ partials, int splits,
+                                                         size_t count4, float4 *__restrict__ c) {
+    __shared__ float4 sm[kReduceGroups][kReduceOutputs];
+    const int o = threadIdx.x % kReduceOutputs, grp = threadIdx.x / kReduceOutputs;
+    const size_t i = (size_t)blockIdx.x * kReduceOutputs + o;
+    const int per = (splits + kReduceGroups - 1) / kReduceGroups;
+    const int beg = grp * per, end = beg + per < splits ? beg + per : splits;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    int p = 0;
-    for (; p + 8 <= splits; p += 8) {
-        float4 v[8];
+    if (i < count4) {
+        int p = beg;
+        for (; p + 4 <= end; p += 4) {
+            float4 v[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = partials[(size_t)(p + u) * count4 + i];
+            for (int u = 0; u < 4; ++u) v[u] = partials[(size_t)(p + u) * count4 + i];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            s.x += v[u].x;
-            s.y += v[u].y;
-            s.z += v[u].z;
-            s.w += v[u].w;
+            for (int u = 0; u < 4; ++u) {
+                s.x += v[u].x;
+                s.y += v[u].y;
+                s.z += v[u].z;
+                s.w += v[u].w;
+            }
+        }
+        for (; p < end; ++p) {
+            const float4 v = partials[(size_t)p * count4 + i];
+            s.x += v.x;
+            s.y += v.y;
+            s.z += v.z;
+            s.w += v.w;
         }
     }
-    for (; p < splits; ++p) {
-        const float4 v = partials[(size_t)p * count4 + i];
-        s.x += v.x;
-        s.y += v.y;
-        s.z += v.z;
-        s.w += v.w;
+    sm[grp][o] = s;
+    __syncthreads();
+    if (grp == 0 && i < count4) {
+        float4 t = sm[0][o];
+#pragma unroll
+        for (int q = 1; q < kReduceGroups; ++q) {
+            t.x += sm[q][o].x;
+            t.y += sm[q][o].y;
+            t.z += sm[q][o].z;
+            t.w += sm[q][o].w;
+        }
+        c[i] = t;
     }
-    c[i] = s;
 }
 
 // as k_reduce_partials, then max(., 0) when relu is set
@@ -406,7 +428,7 @@ int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
 
 int reduce_partials(const float *partials, int splits, size_t count, float *c, hipStream_t st) {
     const size_t count4 = count / 4;   // leading dimensions are multiples of 16
-    k_reduce_partials<<<dim3((unsigned)((count4 + 63) / 64)), dim3(64), 0, st>>>(
+    k_reduce_partials<<<dim3((unsigned)((count4 + kReduceOutputs - 1) / kReduceOutputs)), dim3(256), 0, st>>>(
         reinterpret_cast<const float4 *>(partials), splits, count4, reinterpret_cast<float4 *>(c));
     GCN_LAUNCH_CHECK();
     return GCN_OK;

@@ -56,13 +56,13 @@ def _bernoulli_mask(seed: int, n: int, p: float) -> np.ndarray:
     return (rng.uniform(seed, 7100, n) < p).astype(np.uint8)
 
 
-def tiny(seed: int = 0, n: int = 2048, messy: bool = False) -> Workload:
-    """Config 1: Erdos-Renyi, average degree 4, 256 -> 16 -> 7."""
+def tiny(seed: int = 0, n: int = 2048, messy: bool = False, classes: int = 7) -> Workload:
+    """Config 1: Erdos-Renyi, average degree 4, 256 -> 16 -> 7 (or another number of classes)."""
     m = 2 * n
     rowptr, col = graphs.erdos_renyi_gnm(n, m, seed)
     if messy:
         rowptr, col = graphs.messy_copy(n, rowptr, col, seed)
-    dims = [256, 16, 7]
+    dims = [256, 16, classes]
     x = _features(seed, n, dims[0])
     labels = rng.integers(seed, 7200, n, dims[-1]).astype(np.int32)
     mask = _bernoulli_mask(seed, n, 0.5)

@@ -164,6 +164,17 @@ def test_tiny_config_full_step(B, oracle):
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
+@pytest.mark.parametrize("classes", [2, 16, 17, 64, 65, 100, 200])
+def test_loss_with_few_and_many_classes(B, oracle, classes):
+    """Up to 64 classes a group of 16 lanes takes a vertex, above that a whole wave: both against the oracle, on
+    both sides of the switch and of a lane group's width."""
+    wl = workloads.tiny(n=1500, classes=classes)
+    g = H.gpu_graph(B, wl)
+    _, gpu = H.gpu_epoch(B, g, wl)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
 @pytest.mark.parametrize("make", [lambda: workloads.chung_lu_mid(scale=0.1),
                                   lambda: workloads.reddit_partition(scale=0.08),
                                   lambda: workloads.rmat_large(scale=0.004)],
