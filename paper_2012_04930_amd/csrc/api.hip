@@ -992,14 +992,22 @@ int gcn_sgd_step(gcn_model *m, float lr, void *stream) {
         return GCN_EINVAL;
     }
     hipStream_t st = (hipStream_t)stream;
-    for (auto &ly : m->layers) {
-        int rc = sgd_update(ly.w, ly.dw, (size_t)ly.ld_in * ly.ld_out, lr, st);
-        if (rc) return rc;
-        if (m->dtype == GCN_BF16) {
+    SgdLayers ls{};
+    size_t total = 0;
+    for (auto &ly : m->layers) {   // at most kMaxLayers of them: checked when the model was created
+        ls.w[ls.n] = ly.w;
+        ls.dw[ls.n] = ly.dw;
+        total += (size_t)ly.ld_in * ly.ld_out;
+        ls.end[ls.n] = total;
+        ls.n += 1;
+    }
+    int rc = sgd_update(ls, lr, st);
+    if (rc) return rc;
+    if (m->dtype == GCN_BF16)
+        for (auto &ly : m->layers) {
             rc = weight_copies(ly.w, ly.ld_in, ly.ld_out, ly.wb, ly.wbt, ly.ld_in, st);
             if (rc) return rc;
         }
-    }
     m->epoch += 1;
     m->have_forward = m->have_loss = m->have_backward = false;
     return GCN_OK;

@@ -173,7 +173,15 @@ int loss_forward(int64_t n, int classes, const float *logits, int ld, const int3
                  const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
                  long long *corr_part, float *result /* [0] loss, [1] accuracy, as float */,
                  long long *result_correct, hipStream_t st);
-int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st);
+// w_l -= lr dw_l for every layer l in one launch; end[l] = number of elements of layers 0..l together
+constexpr int kMaxLayers = 16;
+struct SgdLayers {
+    float *w[kMaxLayers];
+    const float *dw[kMaxLayers];
+    size_t end[kMaxLayers];
+    int n;
+};
+int sgd_update(const SgdLayers &ls, float lr, hipStream_t st);
 int adam_update(float *w, const float *dw, float *m, float *v, size_t count, float lr, float beta1, float beta2,
                 float eps, int64_t step, hipStream_t st);
 // every weights[i][0..elems) becomes the mean over i (summed in list order)

@@ -258,9 +258,17 @@ __global__ void k_calibration_copy(const uint4 *__restrict__ src, uint4 *__restr
     if (t < words) dst[t] = src[t];
 }
 
-__global__ void k_sgd(float *__restrict__ w, const float *__restrict__ dw, size_t count, float lr) {
-    size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < count) w[t] = w[t] - lr * dw[t];
+// All layers in one launch: element t of the concatenation belongs to the first layer whose end is beyond it.
+__global__ void k_sgd(SgdLayers ls, float lr) {
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t first = 0;
+    for (int l = 0; l < ls.n; ++l) {
+        if (t < ls.end[l]) {
+            ls.w[l][t - first] = ls.w[l][t - first] - lr * ls.dw[l][t - first];
+            return;
+        }
+        first = ls.end[l];
+    }
 }
 
 // Adam (Kingma & Ba): c1 = 1 - beta1^t, c2 = 1 - beta2^t are formed on the host in double precision.
@@ -435,9 +443,14 @@ int calibration_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
     return GCN_OK;
 }
 
-int sgd_update(float *w, const float *dw, size_t count, float lr, hipStream_t st) {
-    if (count == 0) return GCN_OK;
-    k_sgd<<<dim3(blocks_for((int64_t)count, kThreads)), dim3(kThreads), 0, st>>>(w, dw, count, lr);
+int sgd_update(const SgdLayers &ls, float lr, hipStream_t st) {
+    if (ls.n < 1 || ls.n > kMaxLayers) {
+        set_error("sgd_update: %d layers", ls.n);
+        return GCN_EINVAL;
+    }
+    const size_t total = ls.end[ls.n - 1];
+    if (total == 0) return GCN_OK;
+    k_sgd<<<dim3(blocks_for((int64_t)total, kThreads)), dim3(kThreads), 0, st>>>(ls, lr);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }
