@@ -537,6 +537,7 @@ template <typename TIn, typename TOut>
 int launch_by_width(const SpmmArgs &a, hipStream_t st) {
     const int pieces = (a.cols + Piece<TIn>::kElems - 1) / Piece<TIn>::kElems;   // 16-byte pieces per row
     int rc = GCN_OK;
+    if (pieces > 32 && try_phased<TIn, TOut, 64, 4>(a, st, &rc)) return rc;
     if (pieces > 16 && pieces <= 32 && try_phased<TIn, TOut, 32, 4>(a, st, &rc)) return rc;
     if (pieces > 4 && pieces <= 8 && try_phased<TIn, TOut, 8, 2>(a, st, &rc)) return rc;
     if (pieces > 8 && pieces <= 16 && try_phased<TIn, TOut, 16, 2>(a, st, &rc)) return rc;
