@@ -228,7 +228,7 @@ def main() -> int:
     if "w%d" % dom_w in spmm:
         avg = spmm["w%d" % dom_w]["avg_ms"]
         achieved = gather_bytes(E, n, dom_w, esize) / avg / 1e6
-        tiled = tile_info["in_use"] and esize == 4
+        tiled = tile_info["in_use"]
         roofline = {"bound": "hbm",
                     "kernel": ("aggregation, width %d: k_tiles (dense 32x32 tiles on the matrix cores) beside "
                                "k_spmm_phased | k_spmm_wave + k_spmm_group (residual entries), then k_join_parts; "

@@ -91,15 +91,16 @@ int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_trai
  * runs in two parts when the adjacency pattern has dense blocks, as the partitions of a community-structured
  * graph do (Section 3): the pattern is cut into aligned 32 x 32 tiles; tiles with at least `tile_min_entries`
  * stored entries (tunable, default 128, allowed 64..1024) are kept as 32 words of 32 bits and multiplied on the
- * matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The split is used for
- * float32 matrices when the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this
- * rule, 0 never, 1 whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off
- * per call).  Sums are float32 either way; only their order differs.  A non-finite value in a row of the
+ * matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The split is used when
+ * the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this rule, 0 never, 1
+ * whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off per call), for
+ * matrices of at most 256 columns in either storage type (bfloat16 rows are widened exactly).  Sums are
+ * float32 either way; only their order differs.  A non-finite value in a row of the
  * aggregated matrix reaches, through 0 x inf, all 32 rows of the tiles that cover it.
  * Streams: with the split in use the tile product runs on a stream of default priority that the graph owns,
  * beside the gather kernel on the caller's stream; fork and join are done with events, so the caller's stream
  * order is kept, and a third launch adds the two parts.  Tunable "spmm_overlap": 1 = this (default), 0 = one
- * launch after the other on the caller's stream.  Because that stream and its events belong to the graph, calls that aggregate over one graph
+ * launch after the other on the caller's stream (float32 storage; bfloat16 matrices are then gathered whole).  Because that stream and its events belong to the graph, calls that aggregate over one graph
  * (gcn_aggregate, gcn_model_create, gcn_forward, gcn_backward) must not overlap in time, whatever streams they
  * are given.
  * gcn_graph_tile_info: number of dense tiles, stored entries inside them, 1 if the split is in use.

@@ -107,6 +107,7 @@ struct gcn_model {
     float *partials = nullptr;
     size_t partial_floats = 0;
     float *tile_sums = nullptr;     // n x widest aggregated matrix: the tile product's output when it runs beside the gather
+    float *gather_sums = nullptr;   // the same for the gather's plain sums (bfloat16 models only)
     float *chunk_sums = nullptr;    // chunks x widest: sums of the chunks of split rows
     double *loss_part = nullptr;
     long long *corr_part = nullptr;
@@ -137,12 +138,19 @@ size_t chunk_sum_floats(const gcn_graph *g, int cols) {
     return (size_t)chunks * (size_t)cols;
 }
 
-// tile_sums: n x cols floats for the tile product when it runs beside the gather kernel (null: one after the other)
+// tile_sums: n x cols floats for the tile product when it runs beside the gather kernel (null: one after the other);
+// gather_sums: the same again for the gather kernel's plain sums when the output is bfloat16 (else null)
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
-                   int cols, int width, int epilogue, float *tile_sums, float *chunk_sums) {
+                   int cols, int width, int epilogue, float *tile_sums, float *chunk_sums,
+                   float *gather_sums = nullptr) {
     SpmmArgs a{};
-    // the dense-tile form handles float32 matrices; everything else gathers over the whole pattern
-    const bool tiles = g->use_tiles && t_dtype == GCN_F32 && out_dtype == GCN_F32 && tunable("spmm_tiles", -1) != 0;
+    // The dense-tile form: float32 matrices either way (side by side or one after the other); bfloat16 inputs
+    // side by side only, and with a bfloat16 output only with a buffer for the gather's float32 sums.  Everything
+    // else gathers over the whole pattern.
+    const bool side_by_side = tile_sums && g->side && tunable("spmm_overlap", 1) != 0;
+    const bool tiles = g->use_tiles && tunable("spmm_tiles", -1) != 0 && cols <= 256 &&
+                       ((t_dtype == GCN_F32 && out_dtype == GCN_F32) ||
+                        (t_dtype == GCN_BF16 && side_by_side && (out_dtype == GCN_F32 || gather_sums)));
     const PrepBuffers &pb = tiles ? g->res : g->pb;
     a.rowptr = pb.rowptr;
     a.col = pb.col;
@@ -169,6 +177,7 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
         a.bits = g->tiles.bits;
         a.n_rt = g->tiles.n_rt;
         if (tile_sums && g->side) {
+            a.gather_sums = gather_sums;
             a.tile_sums = tile_sums;
             a.side = g->side;
             a.ev_fork = g->ev_fork;
@@ -276,7 +285,8 @@ void carve_model(Carver &c, gcn_model &m) {
         const int slab = slab_max < m.g->ldf ? slab_max : m.g->ldf;
         widest = slab > widest ? slab : widest;
     }
-    m.tile_sums = (m.g->use_tiles && m.dtype == GCN_F32) ? c.take<float>((size_t)n * widest) : nullptr;
+    m.tile_sums = m.g->use_tiles ? c.take<float>((size_t)n * widest) : nullptr;
+    m.gather_sums = (m.g->use_tiles && m.dtype == GCN_BF16) ? c.take<float>((size_t)n * widest) : nullptr;
     m.chunk_sums = c.take<float>(chunk_sum_floats(m.g, widest));
     m.partial_floats = pf;
     m.partials = c.take<float>(pf);
@@ -740,7 +750,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
         for (int c0 = 0; !rc && c0 < g->ldf; c0 += slab) {
             const int cols = g->ldf - c0 < slab ? g->ldf - c0 : slab;
             SpmmArgs a = spmm_args(g, (const char *)m->xs + c0 * es, dtype, g->ldf, (char *)m->pax + c0 * es, dtype,
-                                   g->ldf, cols, g->f, kEpiNone, m->tile_sums, m->chunk_sums);
+                                   g->ldf, cols, g->f, kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums);
             rc = spmm_launch(a, st);
         }
     }
@@ -875,7 +885,7 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
         SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
-                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums, m->chunk_sums);
+                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums);
         a.drop_threshold = act.drop_threshold;
         a.keep_scale = act.keep_scale;
         a.drop_key = act.drop_key;
@@ -955,7 +965,7 @@ int gcn_backward(gcn_model *m, void *stream) {
         }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
         SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone,
-                               m->tile_sums, m->chunk_sums);
+                               m->tile_sums, m->chunk_sums, m->gather_sums);
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G

@@ -236,6 +236,7 @@ struct SpmmArgs {
     // floats] while the gather kernel writes plain sums to out on the caller's stream; a third launch adds the two
     // and finishes the rows.  Without them the gather kernel follows the tile product and finishes the rows itself.
     float *tile_sums;
+    float *gather_sums;   // [n x cols floats] the gather kernel's plain sums when the output itself is bfloat16
     hipStream_t side;
     hipEvent_t ev_fork, ev_join;
     int finish_mode;     // set by spmm_launch, see SpmmFinish

@@ -395,9 +395,11 @@ __global__ __launch_bounds__(kThreads) void k_spmm_group(const int64_t *__restri
 }
 
 // ------------------------------------------------------------------------------------------------ joining the parts
-// out[r, c .. c + 4) = finish(d_r^-1/2 (out[r, c ..] + tile_sums[r, c ..])): the gather kernel's plain sums over
-// the residual entries plus the tile product's sums, one thread per four columns.
-__global__ __launch_bounds__(kThreads) void k_join_parts(float *__restrict__ out, int ld_out,
+// out[r, c .. c + 4) = finish(d_r^-1/2 (sums[r, c ..] + tile_sums[r, c ..])): the gather kernel's plain sums over
+// the residual entries (float32: left in out itself, sums == out) plus the tile product's sums, one thread per four
+// columns.
+template <typename TOut>
+__global__ __launch_bounds__(kThreads) void k_join_parts(TOut *out, int ld_out, const float *sums, int ld_sums,
                                                          const float *__restrict__ tile_sums, int ld_tile,
                                                          const float *__restrict__ dinv, int64_t n, int cols, Epi ep) {
     const int quads = cols / 4;
@@ -405,16 +407,15 @@ __global__ __launch_bounds__(kThreads) void k_join_parts(float *__restrict__ out
     if (i >= n * quads) return;
     const int64_t r = i / quads;
     const int c0 = (int)(i % quads) * 4;
-    float *o = out + r * ld_out + c0;
-    const float4 a = *reinterpret_cast<const float4 *>(o);
+    const float4 a = *reinterpret_cast<const float4 *>(sums + r * ld_sums + c0);
     const float4 b = *reinterpret_cast<const float4 *>(tile_sums + r * ld_tile + c0);
     const float d = dinv[r];
-    float4 v;
-    v.x = finish((a.x + b.x) * d, ep, r, c0);
-    v.y = finish((a.y + b.y) * d, ep, r, c0 + 1);
-    v.z = finish((a.z + b.z) * d, ep, r, c0 + 2);
-    v.w = finish((a.w + b.w) * d, ep, r, c0 + 3);
-    *reinterpret_cast<float4 *>(o) = v;
+    float v[4];
+    v[0] = finish((a.x + b.x) * d, ep, r, c0);
+    v[1] = finish((a.y + b.y) * d, ep, r, c0 + 1);
+    v[2] = finish((a.z + b.z) * d, ep, r, c0 + 2);
+    v[3] = finish((a.w + b.w) * d, ep, r, c0 + 3);
+    store_elems<4>(out + r * ld_out + c0, v);
 }
 
 // true when every byte of the input (n + 1 rows) is addressable with a 32-bit offset
@@ -570,7 +571,14 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     SpmmArgs b = a;
     b.finish_mode = kFinishRow;
     int rc = GCN_OK;
-    const bool overlap = a.tile_ptr && a.tile_sums && a.side && a.ev_fork && a.ev_join && tunable("spmm_overlap", 1) != 0;
+    // side by side needs somewhere to leave the gather's plain float32 sums: the output itself, or gather_sums
+    const bool overlap = a.tile_ptr && a.tile_sums && a.side && a.ev_fork && a.ev_join &&
+                         (a.out_dtype == GCN_F32 || a.gather_sums) && tunable("spmm_overlap", 1) != 0;
+    if (a.tile_ptr && !overlap && a.out_dtype != GCN_F32) {
+        set_error("aggregation: dense tiles with a bfloat16 output need the side stream and both sum buffers");
+        timing_end(st);
+        return GCN_EINVAL;
+    }
     if (a.tile_ptr && overlap) {
         // fork: the tile product on the side stream, the gather over the residual entries on the caller's
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
@@ -578,13 +586,18 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, true, a.side);
         if (rc == GCN_OK) rc = hip_status(hipEventRecord(a.ev_join, a.side), "hipEventRecord");
         b.finish_mode = kFinishPlainSum;
+        if (a.out_dtype != GCN_F32) {
+            b.out = a.gather_sums;
+            b.out_dtype = GCN_F32;
+            b.ld_out = a.cols;
+        }
     } else if (a.tile_ptr) {
         rc = tiles_launch(a, static_cast<float *>(a.out), a.ld_out, false, st);
         b.finish_mode = kFinishAddStored;
     }
     if (rc == GCN_OK) {
-        if (a.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, st);
-        else if (a.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, st);
+        if (b.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, st);
+        else if (b.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, st);
         else rc = launch_by_width<bf16_t, bf16_t>(b, st);
     }
     if (a.tile_ptr && overlap) {
@@ -594,8 +607,15 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         if (rc == GCN_OK) {
             Epi ep{a.epilogue == kEpiRelu ? kActRelu : kActNone, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
             const int64_t quads = a.n * (a.cols / 4);
-            k_join_parts<<<dim3((unsigned)((quads + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-                static_cast<float *>(a.out), a.ld_out, a.tile_sums, a.cols, a.dinv, a.n, a.cols, ep);
+            const dim3 grid((unsigned)((quads + kThreads - 1) / kThreads));
+            if (a.out_dtype == GCN_F32)
+                k_join_parts<float><<<grid, dim3(kThreads), 0, st>>>(static_cast<float *>(a.out), a.ld_out,
+                                                                    static_cast<const float *>(a.out), a.ld_out,
+                                                                    a.tile_sums, a.cols, a.dinv, a.n, a.cols, ep);
+            else
+                k_join_parts<bf16_t><<<grid, dim3(kThreads), 0, st>>>(static_cast<bf16_t *>(a.out), a.ld_out,
+                                                                     a.gather_sums, a.cols, a.tile_sums, a.cols,
+                                                                     a.dinv, a.n, a.cols, ep);
             rc = hip_status(hipGetLastError(), "k_join_parts launch");
         }
     }

@@ -174,6 +174,20 @@ __device__ inline void load_elems(const float *p, float (&v)[4]) {
     v[2] = q.z;
     v[3] = q.w;
 }
+// the same for bfloat16 rows (a 2-, 4- or 8-byte load), widened exactly
+__device__ inline void load_elems(const bf16_t *p, float (&v)[1]) { v[0] = widen(*p); }
+__device__ inline void load_elems(const bf16_t *p, float (&v)[2]) {
+    typedef bf16_t bvec2 __attribute__((ext_vector_type(2)));
+    const bvec2 q = *reinterpret_cast<const bvec2 *>(p);
+    v[0] = (float)q[0];
+    v[1] = (float)q[1];
+}
+__device__ inline void load_elems(const bf16_t *p, float (&v)[4]) {
+    typedef bf16_t bvec4 __attribute__((ext_vector_type(4)));
+    const bvec4 q = *reinterpret_cast<const bvec4 *>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (float)q[i];
+}
 __device__ inline void store_elems_raw(float *p, const float (&v)[1]) { *p = v[0]; }
 __device__ inline void store_elems_raw(float *p, const float (&v)[2]) {
     *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
@@ -343,23 +357,29 @@ int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_
 }
 
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, bool beside_gather, hipStream_t st) {
-    if (a.t_dtype != GCN_F32 || a.out_dtype != GCN_F32 || a.cols > 256) {
-        set_error("dense tiles: float32 matrices of at most 256 columns only");
+    if (a.cols > 256) {
+        set_error("dense tiles: at most 256 columns");
         return GCN_EINVAL;
     }
     const int n_rt = (int)a.n_rt;
     const unsigned grid = (unsigned)((n_rt + kXcds - 1) / kXcds * kXcds);
-    const float *t = static_cast<const float *>(a.t);
     float *out = dst;
-    const bool narrow = (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * sizeof(float) <= 0xffffffffull;
-#define GCN_TILES(CB, WB, OCC)                                                                                        \
+    const size_t es = a.t_dtype == GCN_BF16 ? 2 : 4;
+    const bool narrow = (uint64_t)(a.n + 1) * (uint64_t)a.ld_t * es <= 0xffffffffull;
+#define GCN_TILES_T(TIn, CB, WB, OCC)                                                                                 \
     do {                                                                                                              \
+        const TIn *t = static_cast<const TIn *>(a.t);                                                                 \
         if (narrow)                                                                                                   \
-            k_tiles<float, CB, WB, true, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                 \
+            k_tiles<TIn, CB, WB, true, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                   \
                 a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, ld_dst, a.cols);                         \
         else                                                                                                          \
-            k_tiles<float, CB, WB, false, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                \
+            k_tiles<TIn, CB, WB, false, OCC><<<dim3(grid), dim3(kThreads), 0, st>>>(                                  \
                 a.tile_ptr, a.tile_col, a.bits, a.n, n_rt, t, a.ld_t, out, ld_dst, a.cols);                         \
+    } while (0)
+#define GCN_TILES(CB, WB, OCC)                                                                                        \
+    do {                                                                                                              \
+        if (a.t_dtype == GCN_BF16) GCN_TILES_T(bf16_t, CB, WB, OCC);                                                  \
+        else GCN_TILES_T(float, CB, WB, OCC);                                                                         \
     } while (0)
     // Measured on a 47.5 k-vertex partition with 43 k dense tiles: four column blocks per wave at two waves per
     // SIMD beat one wave per SIMD (a second workgroup covers the first one's start and end) and two blocks per wave.
@@ -372,6 +392,7 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, bool beside_gather, 
     }
     else GCN_TILES(4, 2, 2);
 #undef GCN_TILES
+#undef GCN_TILES_T
     GCN_LAUNCH_CHECK();
     return GCN_OK;
 }

@@ -110,10 +110,18 @@ def test_aggregate_with_tiles_matches_oracle(B, oracle, knobs, case, width):
     knobs("spmm_tiles", 1)
     H.assert_close(plain, ref, what="gather only, width %d" % width)
     np.testing.assert_allclose(got, plain, rtol=0, atol=4e-6 * np.abs(ref).max())
-    # bfloat16 storage does not take the tile form and must still be right on such a graph
-    if width in (41, 128):
-        got16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
-        H.assert_close(got16, ref, rtol=H.RTOL_BF16, what="bf16 on a tiled graph")
+    # bfloat16 rows take the tile form too (side by side only): against the oracle, and against the whole-pattern
+    # gather of the same rounded rows, which adds the same terms in another order
+    got16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
+    H.assert_close(got16, ref, rtol=H.RTOL_BF16, what="bf16 rows, tiles + residual, width %d" % width)
+    knobs("spmm_tiles", 0)
+    plain16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
+    knobs("spmm_tiles", 1)
+    np.testing.assert_allclose(got16, plain16, rtol=0, atol=4e-6 * np.abs(ref).max())
+    knobs("spmm_overlap", 0)                  # one after the other is a float32 form: bfloat16 rows are gathered whole
+    seq16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
+    knobs("spmm_overlap", 1)
+    np.testing.assert_array_equal(seq16, plain16)
 
 
 @pytest.mark.parametrize("width", [41, 128, 256])
@@ -163,6 +171,24 @@ def test_full_step_with_tiles(B, oracle, knobs, dropout_p):
         _, gpu = H.gpu_epoch(B, g, wl, dropout_p=dropout_p, seed=5, cache_ax=cache_ax)
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=dropout_p, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new)
+
+
+@pytest.mark.parametrize("dropout_p", [0.0, 0.5])
+def test_full_step_with_tiles_in_bfloat16_storage(B, oracle, knobs, dropout_p):
+    """Hidden activations and gradients are bfloat16: the gather leaves float32 sums in a buffer of its own and the
+    join rounds once, as the single-launch form does."""
+    wl = workloads.reddit_partition(scale=0.08)
+    knobs("spmm_tiles", 1)
+    knobs("tile_min_entries", 64)
+    g = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+    for cache_ax, overlap in ((0, 1), (2, 1), (0, 0)):
+        knobs("spmm_overlap", overlap)
+        _, gpu = H.gpu_epoch(B, g, wl, dropout_p=dropout_p, seed=5, cache_ax=cache_ax, dtype=B.GCN_BF16)
+        _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=dropout_p, seed=5, bf16=True)
+        # inverted dropout multiplies kept values, and their rounding errors, by 1/(1-p) but the rms of the tensor
+        # (a fraction p of it zeroed) only by 1/sqrt(1-p): the bfloat16 bound scales with the ratio
+        H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16 / np.sqrt(1.0 - dropout_p))
 
 
 def test_epoch_captured_in_a_hip_graph_replays_like_eager_launches(B, knobs):
