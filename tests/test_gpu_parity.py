@@ -256,6 +256,16 @@ def test_benchmark_config_c3_full_size(B, oracle):
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
+def test_benchmark_config_c3_full_size_in_bfloat16_storage(B, oracle):
+    """The launch configuration `bench.py --dtype bf16` times: dense tiles on widened rows beside the gather."""
+    wl = workloads.reddit_partition()
+    g = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+    _, gpu = H.gpu_epoch(B, g, wl, dtype=B.GCN_BF16, cache_ax=0)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True)
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
+
+
 def test_config_c2_full_size(B, oracle):
     wl = workloads.chung_lu_mid()                      # 100,000 vertices, light and heavy rows mixed
     g = H.gpu_graph(B, wl)
