@@ -478,9 +478,13 @@ int launch(const SpmmArgs &a, hipStream_t st) {
 // fits, and a wave gets at most 8 rows with the whole grid resident.  Knob "spmm_phased": -1 automatic
 // (default), 0 never, 1 whenever the shape allows.
 constexpr int64_t kL2Bytes = 4 << 20;
-// A phase's input rows may take 5/4 of one L2: on the benchmark partition width 128 is fastest at 3.0 MB per phase
-// (1.5 MB: +19 %, 6.1 MB: +14 %) and width 48 at 4.6 MB (2.3 MB: +6 %, 9.1 MB: +5 %).
-constexpr int64_t kPhaseBytes = 5 << 20;
+// Input rows per phase, in bytes.  Measured on the benchmark partition (time of the aggregation inside an epoch):
+//   512-byte rows (float32, width 128):  1.5 MB +19 %, 3.0 MB best, 6.1 MB +14 %
+//   256-byte rows (bfloat16, width 128): 1.5 MB +14 %, 3.0 MB +4 %, 6.1 MB best
+//   192-byte rows (float32, width 48):   2.3 MB +6 %, 4.6 MB best, 9.1 MB +5 %
+// so rows of at least 512 bytes (a lane group of 32 or 64 lanes) get up to 5 MB, narrower ones up to 6.5 MB.
+constexpr int64_t kPhaseBytesWide = 5 << 20;
+constexpr int64_t kPhaseBytesNarrow = (13 << 20) / 2;
 
 template <typename TIn, typename TOut, int LPR, int U>
 bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
@@ -497,11 +501,13 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     const TIn *t = static_cast<const TIn *>(a.t);
     TOut *out = static_cast<TOut *>(a.out);
     const int zero_row = (int)a.n;
-    // column ranges per phase (1, 2, 4 or 8): the most whose rows take at most kPhaseBytes.  Knob "phased_group":
+    // column ranges per phase (1, 2, 4 or 8): the most whose rows take at most kPhaseBytesWide / Narrow.  Knob "phased_group":
     // 0 = this rule.
     int64_t group = tunable("phased_group", 0);
     if (group <= 0)
-        for (group = kColBlocks / 2; group > 1 && group * block * row_bytes > kPhaseBytes;) group /= 2;
+        for (group = kColBlocks / 2;
+             group > 1 && group * block * row_bytes > (LPR >= 32 ? kPhaseBytesWide : kPhaseBytesNarrow);)
+            group /= 2;
 #define GCN_PHASED(RR, GG)                                                                                           \
     k_spmm_phased<TIn, TOut, LPR, U, RR, GG><<<dim3(grid), dim3(kThreads), 0, st>>>(                                  \
         a.rowptr, a.col, a.segoff, a.prow, W, a.dinv, zero_row, a.n, block, t, a.ld_t, out, a.ld_out, \
