@@ -114,6 +114,16 @@ int gcn_graph_tile_info(const gcn_graph *g, int64_t *n_tiles, int64_t *nnz_dense
 int gcn_graph_get_tiles(const gcn_graph *g, int64_t *tile_ptr, int32_t *tile_col, uint32_t *bits,
                         int64_t *res_rowptr, int32_t *res_col, int64_t *res_nnz, void *stream);
 
+/* The masked pattern.  In the backward pass of the last layer the aggregated matrix is dLoss/dlogits of Section 2.2's
+ * loss, whose rows are zero for every vertex outside the train mask, so that aggregation runs over the pattern it
+ * would gather over anyway (the residual one when dense tiles are in use, else A + I) without the columns of
+ * those vertices.  Built by gcn_graph_create when the train mask holds at most four fifths of the vertices
+ * (tunable "spmm_masked": 1 this rule (default), 0 never; read at gcn_graph_create); the sums do not change, only
+ * zero terms are left out.
+ * gcn_graph_get_masked_pattern (an error when the graph has none; rowptr [dev, n+1 int64] and col [dev, int32,
+ * room for *nnz entries; ask for *nnz first] may be NULL; asynchronous on `stream` except *nnz [host]). */
+int gcn_graph_get_masked_pattern(const gcn_graph *g, int64_t *rowptr, int32_t *col, int64_t *nnz, void *stream);
+
 /* Copies the canonical arrays to caller buffers [dev]: rowptr (n+1 int64), col (E int32), deg (n int32),
  * dinv (n float32).  Any pointer may be NULL.  Asynchronous on `stream`. */
 int gcn_graph_get_csr(const gcn_graph *g, int64_t *rowptr, int32_t *col, int32_t *deg, float *dinv, void *stream);
@@ -247,6 +257,8 @@ int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
  *                                    there is one; read by gcn_graph_create, 0 also per call
  *   "tile_min_entries"  64..1024     entries that make a 32 x 32 tile dense (default 128); read by gcn_graph_create
  *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
+ *   "spmm_masked"       1 / 0        masked pattern for the last layer's backward aggregation when the train mask
+ *                                    holds at most 4/5 of the vertices (default) / never; read by gcn_graph_create
  *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows
  *   "phased_balance"    1 / 0        XCD row ranges of the phased schedule by entries (default) / by rows; read by
  *                                    gcn_graph_create

@@ -23,7 +23,7 @@ STATUS = {0: "GCN_OK", -1: "GCN_EINVAL", -2: "GCN_EGRAPH", -3: "GCN_ELABEL", -4:
 
 EXPORTS = [
     "gcn_last_error", "gcn_graph_workspace_bytes", "gcn_graph_create", "gcn_graph_destroy", "gcn_graph_info",
-    "gcn_graph_get_csr", "gcn_graph_tile_info", "gcn_graph_get_tiles", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
+    "gcn_graph_get_csr", "gcn_graph_tile_info", "gcn_graph_get_tiles", "gcn_graph_get_masked_pattern", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
     "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
@@ -60,6 +60,7 @@ def lib():
         L.gcn_graph_get_csr.argtypes = [vp, vp, vp, vp, vp, vp]
         L.gcn_graph_tile_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
         L.gcn_graph_get_tiles.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(i64), vp]
+        L.gcn_graph_get_masked_pattern.argtypes = [vp, vp, vp, C.POINTER(i64), vp]
         L.gcn_aggregate_workspace_bytes.argtypes = [vp, i32, C.c_int, C.POINTER(sz)]
         L.gcn_aggregate.argtypes = [vp, vp, vp, i32, C.c_int, vp, sz, vp]
         L.gcn_model_workspace_bytes.argtypes = [vp, i32, C.POINTER(i32), C.c_int, C.POINTER(sz)]
@@ -189,6 +190,16 @@ def gcn_graph_get_tiles(g: Graph):
                                      res_rowptr.data_ptr(), res_col.data_ptr(), C.byref(got), _stream()))
     assert got.value == res_nnz
     return tile_ptr, tile_col, bits, res_rowptr, res_col[:res_nnz]
+
+
+def gcn_graph_get_masked_pattern(g: Graph):
+    """-> (rowptr, col) of the pattern the last layer's backward aggregation gathers over; raises if there is none."""
+    nnz = C.c_int64()
+    _check(lib().gcn_graph_get_masked_pattern(g.handle, None, None, C.byref(nnz), _stream()))
+    rowptr = torch.empty(g.n + 1, dtype=torch.int64, device="cuda")
+    col = torch.empty(max(nnz.value, 1), dtype=torch.int32, device="cuda")
+    _check(lib().gcn_graph_get_masked_pattern(g.handle, rowptr.data_ptr(), col.data_ptr(), C.byref(nnz), _stream()))
+    return rowptr, col[:nnz.value]
 
 
 def gcn_aggregate(g: Graph, x: torch.Tensor, dtype: int = GCN_F32, ws: torch.Tensor | None = None) -> torch.Tensor:

@@ -134,7 +134,8 @@ bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
 // floats for the chunk sums of one aggregation of `cols` columns over either form of the pattern
 size_t chunk_sum_floats(const gcn_graph *g, int cols) {
-    const int64_t chunks = g->rows.n_chunks > g->res_rows.n_chunks ? g->rows.n_chunks : g->res_rows.n_chunks;
+    int64_t chunks = g->rows.n_chunks > g->res_rows.n_chunks ? g->rows.n_chunks : g->res_rows.n_chunks;
+    if (g->bwd_rows.n_chunks > chunks) chunks = g->bwd_rows.n_chunks;
     return (size_t)chunks * (size_t)cols;
 }
 
@@ -142,7 +143,7 @@ size_t chunk_sum_floats(const gcn_graph *g, int cols) {
 // gather_sums: the same again for the gather kernel's plain sums when the output is bfloat16 (else null)
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
                    int cols, int width, int epilogue, float *tile_sums, float *chunk_sums,
-                   float *gather_sums = nullptr) {
+                   float *gather_sums = nullptr, bool rows_zero_outside_mask = false) {
     SpmmArgs a{};
     // The dense-tile form: float32 matrices either way (side by side or one after the other); bfloat16 inputs
     // side by side only, and with a bfloat16 output only with a buffer for the gather's float32 sums.  Everything
@@ -151,17 +152,21 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
     const bool tiles = g->use_tiles && tunable("spmm_tiles", -1) != 0 && cols <= 256 &&
                        ((t_dtype == GCN_F32 && out_dtype == GCN_F32) ||
                         (t_dtype == GCN_BF16 && side_by_side && (out_dtype == GCN_F32 || gather_sums)));
-    const PrepBuffers &pb = tiles ? g->res : g->pb;
+    // rows_zero_outside_mask: the caller vouches that the input's rows of vertices outside the train mask are zero;
+    // then the pattern without their columns gives the same sums (it was cut from the pattern of the default form)
+    const bool masked = rows_zero_outside_mask && g->use_bwd && tiles == g->use_tiles;
+    const PrepBuffers &pb = masked ? g->bwd : (tiles ? g->res : g->pb);
     a.rowptr = pb.rowptr;
     a.col = pb.col;
     a.perm = pb.perm;
     a.dinv = g->pb.dinv;
     a.segoff = pb.segoff;
     a.prow = pb.prow;
-    a.phased_w = (tiles ? g->res_rows : g->rows).phased_w;
-    a.phased_r = (tiles ? g->res_rows : g->rows).phased_r;
+
     a.n = g->n;
-    const gcn_graph::RowClasses &rc = tiles ? g->res_rows : g->rows;
+    const gcn_graph::RowClasses &rc = masked ? g->bwd_rows : (tiles ? g->res_rows : g->rows);
+    a.phased_w = rc.phased_w;
+    a.phased_r = rc.phased_r;
     a.n_heavy = rc.n_heavy;
     a.n_light = rc.n_light;
     a.n_split = rc.n_split;
@@ -245,6 +250,19 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.res.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
     g.res.row_start = c.take<int32_t>(16);
     g.res.flags = c.take<int32_t>(16);
+    g.bwd = g.pb;   // as the residual pattern: its own pattern and schedule, the rest shared
+    g.bwd.rowptr = c.take<int64_t>(n + 1);
+    g.bwd.col = c.take<int32_t>(cap + kColSlack);
+    g.bwd.deg = c.take<int32_t>(n);
+    g.bwd.perm = c.take<int32_t>(n);
+    g.bwd.split_cnt = c.take<int32_t>(g.pb.split_cap);
+    g.bwd.chunk_off = c.take<int64_t>(g.pb.split_cap + 1);
+    g.bwd.chunk_srow = c.take<int32_t>(g.pb.chunk_cap);
+    g.bwd.xcd_start = c.take<int32_t>(16);
+    g.bwd.segoff = phased ? c.take<int32_t>((size_t)n * (kColBlocks + 1)) : nullptr;
+    g.bwd.prow = phased ? c.take<int32_t>(prow_ints) : nullptr;
+    g.bwd.row_start = c.take<int32_t>(16);
+    g.bwd.flags = c.take<int32_t>(16);
     g.x = c.take<char>((size_t)(n + 1) * g.ldf * (g.store_dtype == GCN_BF16 ? 2 : 4));
     g.labels = c.take<int32_t>(n);
     g.mask = c.take<uint8_t>(n);
@@ -499,9 +517,44 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
             HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_join, hipEventDisableTiming));
         }
     }
+    // The last layer's backward aggregation reads dLoss/dlogits, whose rows outside the train mask are zero: a
+    // pattern without those columns, when that drops at least a fifth of the vertices' columns.
+    if (g->n_train * 5 <= n * 4 && tunable("spmm_masked", 1) != 0) {
+        const PrepBuffers &src = g->use_tiles ? g->res : g->pb;
+        FAIL_IF(prep_keep_columns(n, src, g->mask, g->bwd, st));
+        FAIL_IF(fill_zero(g->bwd.flags, 16 * sizeof(int32_t), st));
+        FAIL_IF(prep_schedule(n, g->bwd, st));
+        HIP_OR_FAIL(hipMemcpyAsync(flags, g->bwd.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+        HIP_OR_FAIL(hipMemcpyAsync(&g->bwd_nnz, g->bwd.rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        HIP_OR_FAIL(hipStreamSynchronize(st));
+        HIP_OR_FAIL(read_classes(g->bwd, flags, g->bwd_rows));
+        g->use_bwd = true;
+    }
 #undef FAIL_IF
 #undef HIP_OR_FAIL
     *out = g;
+    return GCN_OK;
+}
+
+int gcn_graph_get_masked_pattern(const gcn_graph *g, int64_t *rowptr, int32_t *col, int64_t *nnz, void *stream) {
+    if (!g) {
+        set_error("gcn_graph_get_masked_pattern: null graph");
+        return GCN_EINVAL;
+    }
+    if (!g->use_bwd) {
+        set_error("gcn_graph_get_masked_pattern: this graph has none");
+        return GCN_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (nnz) *nnz = g->bwd_nnz;
+    hipError_t e = hipSuccess;
+    if (rowptr) e = hipMemcpyAsync(rowptr, g->bwd.rowptr, (size_t)(g->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && col && g->bwd_nnz > 0)
+        e = hipMemcpyAsync(col, g->bwd.col, (size_t)g->bwd_nnz * sizeof(int32_t), hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) {
+        set_error("gcn_graph_get_masked_pattern: copy failed: %s", hipGetErrorString(e));
+        return GCN_EHIP;
+    }
     return GCN_OK;
 }
 
@@ -964,8 +1017,9 @@ int gcn_backward(gcn_model *m, void *stream) {
             continue;
         }
         // G = A_hat dZ_l  (dzs already carries D^-1/2)
+        // (the rows of dZ_L outside the train mask are zero: the loss kernel writes them so)
         SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone,
-                               m->tile_sums, m->chunk_sums, m->gather_sums);
+                               m->tile_sums, m->chunk_sums, m->gather_sums, l == m->L);
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G

@@ -105,6 +105,8 @@ int prep_validate(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_
 int prep_canonical(int64_t n, int64_t nnz_in, const int64_t *rowptr, const int32_t *col, PrepBuffers &pb,
                    hipStream_t st);
 int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st);
+// dst's pattern (rowptr, col, deg) = src's entries whose column c has keep[c] != 0, rows in the same order
+int prep_keep_columns(int64_t n, const PrepBuffers &src, const uint8_t *keep, PrepBuffers &dst, hipStream_t st);
 // Phased aggregation schedule: XCD x owns the rows row_start[x] .. row_start[x + 1] (contiguous id ranges holding
 // equal numbers of entries), each of its W waves R of them.  Not available when an XCD would own more than
 // kPhasedMaxRows rows: 8 rows per wave with 896 waves per XCD (32 CUs x 4 SIMDs x 7 waves, what the kernel's

@@ -10,7 +10,7 @@ struct gcn_graph {
     struct RowClasses {
         int64_t n_heavy = 0, n_light = 0, n_split = 0, n_chunks = 0, xcd_rows_max = 0;
         int phased_w = 0, phased_r = 0;   // 0: no phased schedule for this pattern
-    } rows, res_rows;
+    } rows, res_rows, bwd_rows;
     int32_t f = 0, ldf = 0, n_classes = 0, max_deg = 0;
     int store_dtype = GCN_F32;
     gcn::PrepBuffers pb{};
@@ -19,6 +19,12 @@ struct gcn_graph {
     gcn::PrepBuffers res{};
     int64_t n_tiles = 0, nnz_dense = 0;
     bool use_tiles = false;
+    // The pattern that the default form of the aggregation gathers over (the residual one with tiles in use, else
+    // the whole one) without the columns of vertices outside the train mask: the rows of dLoss/dlogits are zero
+    // there, so the last layer's backward aggregation gathers over this one.  Built when it drops enough entries.
+    gcn::PrepBuffers bwd{};
+    int64_t bwd_nnz = 0;
+    bool use_bwd = false;
     // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;

@@ -508,6 +508,52 @@ int prep_schedule(int64_t n, PrepBuffers &pb, hipStream_t st) {
     return GCN_OK;
 }
 
+namespace {
+
+// One wave per row: the entries whose column c has keep[c] != 0, in their order.
+//   WRITE = false: deg_out[r] = how many;  WRITE = true: col_out filled from rowptr_out[r] on
+template <bool WRITE>
+__global__ __launch_bounds__(kThreads) void k_keep_columns(int64_t n, const int64_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ col,
+                                                           const uint8_t *__restrict__ keep,
+                                                           int32_t *__restrict__ deg_out,
+                                                           const int64_t *__restrict__ rowptr_out,
+                                                           int32_t *__restrict__ col_out) {
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= n) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t beg = rowptr[r], end = rowptr[r + 1];
+    const int64_t out0 = WRITE ? rowptr_out[r] : 0;
+    int count = 0;
+    for (int64_t e0 = beg; e0 < end; e0 += 64) {
+        const int64_t e = e0 + lane;
+        int c = 0;
+        bool kept = false;
+        if (e < end) {
+            c = col[e];
+            kept = keep[c] != 0;
+        }
+        const unsigned long long b = __ballot(kept);
+        if (WRITE && kept) col_out[out0 + count + __popcll(b & ((1ull << lane) - 1ull))] = c;
+        count += __popcll(b);
+    }
+    if (!WRITE && lane == 0) deg_out[r] = count;
+}
+
+}  // namespace
+
+int prep_keep_columns(int64_t n, const PrepBuffers &src, const uint8_t *keep, PrepBuffers &dst, hipStream_t st) {
+    k_keep_columns<false><<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, src.rowptr, src.col, keep,
+                                                                                          dst.deg, nullptr, nullptr);
+    GCN_LAUNCH_CHECK();
+    int rc = exclusive_scan_i32(n, dst.deg, dst.rowptr, dst.blocksum, st);
+    if (rc) return rc;
+    k_keep_columns<true><<<dim3(blocks_for(n, kThreads / 64)), dim3(kThreads), 0, st>>>(n, src.rowptr, src.col, keep,
+                                                                                         nullptr, dst.rowptr, dst.col);
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
 int prep_balance_rows(int64_t n, const int32_t *deg, const int32_t *row_start, int W, int R, int32_t *prow,
                       hipStream_t st) {
     if ((int64_t)W * R > kMaxRangeRows) {

@@ -27,7 +27,7 @@ def knobs(B):
         touched.append(name)
         B.gcn_set_tunable(name, value)
     yield set_
-    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1, "spmm_overlap": 1}
+    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1, "spmm_overlap": 1, "spmm_masked": 1}
     for name in touched:
         B.gcn_set_tunable(name, defaults[name])
 
@@ -143,6 +143,53 @@ def test_tile_product_beside_the_gather_kernel_or_before_it(B, oracle, knobs, wi
         H.assert_close(runs[0], ref, what="overlap %d, width %d" % (overlap, width))
         out[overlap] = runs[0]
     np.testing.assert_allclose(out[1], out[0], rtol=0, atol=4e-6 * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("tiles", [0, 1], ids=["whole_pattern", "residual_pattern"])
+def test_masked_pattern_for_the_last_backward_aggregation_is_bit_exact(B, oracle, knobs, tiles):
+    """The pattern the last layer's backward aggregation gathers over: the default form's pattern (residual with
+    tiles, else A + I) without the columns of vertices outside the train mask, rows and order unchanged."""
+    wl = workloads.reddit_partition(scale=0.05)
+    assert wl.mask.sum() * 5 <= wl.n * 4
+    knobs("spmm_tiles", tiles)
+    knobs("tile_min_entries", 64)
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    if tiles:
+        want = H.tile_split(wl.n, og.rowptr, og.col, 64)
+        rowptr, col = want[3], want[4]
+    else:
+        rowptr, col = og.rowptr, og.col
+    keep = wl.mask[col].astype(bool)
+    rows = np.repeat(np.arange(wl.n), np.diff(rowptr))
+    want_rowptr = np.zeros(wl.n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows[keep], minlength=wl.n), out=want_rowptr[1:])
+    got_rowptr, got_col = [t.cpu().numpy() for t in B.gcn_graph_get_masked_pattern(g)]
+    np.testing.assert_array_equal(got_rowptr, want_rowptr)
+    np.testing.assert_array_equal(got_col, col[keep])
+    assert 0 < len(got_col) < len(col)
+    # a mask that covers (nearly) everything: no such pattern, and the getter says so
+    full = workloads.reddit_partition(scale=0.05)
+    full.mask[:] = 1
+    with pytest.raises(B.GcnError):
+        B.gcn_graph_get_masked_pattern(H.gpu_graph(B, full))
+    knobs("spmm_masked", 0)
+    with pytest.raises(B.GcnError):
+        B.gcn_graph_get_masked_pattern(H.gpu_graph(B, wl))
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16"])
+def test_full_step_with_and_without_the_masked_pattern(B, oracle, knobs, dtype_name):
+    """Leaving out the zero rows' columns changes no sum beyond rounding order: both against the oracle."""
+    bf = dtype_name == "bf16"
+    dtype = B.GCN_BF16 if bf else B.GCN_F32
+    wl = workloads.reddit_partition(scale=0.08)
+    for masked in (1, 0):
+        knobs("spmm_masked", masked)
+        g = H.gpu_graph(B, wl, dtype=dtype)
+        _, gpu = H.gpu_epoch(B, g, wl, dtype=dtype, cache_ax=0)
+        _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=bf)
+        H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16 if bf else H.RTOL_F32)
 
 
 def test_automatic_choice(B, knobs):
