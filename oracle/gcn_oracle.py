@@ -25,7 +25,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gcn_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# GCN_ORACLE_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (the process must then
+# be started with libasan preloaded; tests/test_oracle_sanitized.py does that for the pins)
+_SANITIZE = os.environ.get("GCN_ORACLE_SANITIZE", "0") == "1"
+_LIB = os.path.join(_HERE, "liboracle_san.so" if _SANITIZE else "liboracle.so")
 _lib = None
 
 
@@ -33,7 +36,9 @@ def build(force: bool = False) -> str:
     """Compile gcn_oracle.c with gcc -O2 -fopenmp into liboracle.so (next to the source)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", tmp, _SRC, "-lm"])
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+            if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -219,10 +224,9 @@ def forward(g: Graph, X, Ws, p: float = 0.0, training: bool = False, seed: int =
     return Trace(Ts, Zs, H, keeps)
 
 
-def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0, gate=None) -> Trace:
-    """gate: optional list of arrays, one per hidden layer; when given, the ReLU decision [Z_l > 0] is read
-    from gate[l-1] > 0 instead of this trace's own Z_l.  Parity tests pass the other implementation's
-    activations here so that both sides take that yes/no decision on the same numbers."""
+def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0) -> Trace:
+    """Loss, then the chain rule through the layers in descending order.  The ReLU decision [Z_l > 0] is taken on
+    this trace's own fp64 pre-activations; nothing enters but the trace of `forward` and the inputs."""
     nl = len(Ws)
     tr.loss, tr.correct, tr.n_train, dZL = loss_acc(tr.Z[-1], labels, mask)
     tr.dZ = [None] * nl
@@ -235,7 +239,7 @@ def backward(g: Graph, tr: Trace, Ws, labels, mask, p: float = 0.0, gate=None) -
         tr.dW[l - 1] = matmul_tn(tr.H[l - 1], G)
         if l > 1:
             dH = matmul_nt(G, Ws[l - 1])
-            Zp = tr.Z[l - 2] if gate is None else _f64(gate[l - 2])
+            Zp = tr.Z[l - 2]
             keep = tr.keep[l - 2]
             dZ = np.empty_like(dH)
             lib().orc_relu_dropout_backward(dH.size, _p(Zp, C.c_double),

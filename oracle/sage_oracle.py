@@ -129,9 +129,8 @@ def loss_acc(logits, labels):
     return loss, correct, d / B
 
 
-def backward(t: Trace, W2, labels, S2: int, gate=None):
-    """-> dW1, dW2.  gate: activations to take the ReLU decisions from (the other side's H1), else the oracle's own
-    pre-activations."""
+def backward(t: Trace, W2, labels, S2: int):
+    """-> dW1, dW2.  The ReLU decision [Z1 > 0] is taken on the trace's own pre-activations."""
     W2 = np.asarray(W2, dtype=np.float64)
     B = t.logits.shape[0]
     hidden = t.H1.shape[1]
@@ -141,7 +140,7 @@ def backward(t: Trace, W2, labels, S2: int, gate=None):
     dH = np.empty((B, 1 + S2, hidden))
     dH[:, 0, :] = dC2[:, :hidden]
     dH[:, 1:, :] = (dC2[:, hidden:] / S2)[:, None, :]
-    on = (t.Z1 > 0.0) if gate is None else (np.asarray(gate) > 0.0)
+    on = t.Z1 > 0.0
     t.dZ1 = dH.reshape(B * (1 + S2), hidden) * on
     dW1 = t.C1.T @ t.dZ1
     return dW1, dW2

@@ -1,14 +1,14 @@
 """CPU oracle for the paper's subgraph approximation (TEST INFRASTRUCTURE ONLY).
 
-Builds the augmented partition P_o[p] of Algorithm 1 ("breadth-first random sampling of
-vertices", Section 3.1) and then drops every edge that does not have both ends in it
-(Section 4: after the sampling "all other edges between the subgraphs are dropped").
+Builds the augmented partition P_o[p] of Algorithm 1 (the breadth-first random sampling
+of Section 3.1) and then keeps only the edges with both ends in it (Section 4: cut edges
+that the sampling did not bring in are discarded).
 Plain Python sets and loops: for small graphs only.  Nothing here is shared with, or
 imported by, the GPU package.
 
 Reading of the algorithm (the listing is ambiguous in its recursive step, see the design notes):
   * nts = floor(O * N_p / (M - 1)) vertices are wanted from every other partition op
-    (line 2 of Algorithm 1; N_p counts the vertices of p).
+    (the sizing rule at the top of Algorithm 1; N_p counts the vertices of p).
   * Level 1 of op is every vertex of op adjacent to a vertex of p (`neighbors(p, op)`).
     Level k + 1 is every vertex of op adjacent to a level-k vertex and not in an earlier
     level (`neighbors(selection, op) \\ selection`).
@@ -41,7 +41,7 @@ def sample_key(seed: int, v: int) -> int:
 
 
 def vertices_to_sample(overlap: float, n_p: int, n_parts: int) -> int:
-    """nts of Algorithm 1, line 2 (a single partition has no other partition to sample from)."""
+    """nts, the sizing rule at the top of Algorithm 1 (a single partition has no other partition to sample from)."""
     if n_parts < 2:
         return 0
     return int(np.floor(overlap * n_p / (n_parts - 1)))

@@ -63,3 +63,41 @@ def test_null_handles_and_sizes_of_the_later_entry_points_need_no_gpu():
         assert call() == -1
         assert len(L.gcn_last_error()) > 0
     assert L.gcn_set_tunable(b"spmm_tiles", -1) == 0
+
+
+def test_short_missing_or_misaligned_workspace_is_refused_before_anything_runs():
+    """GCN_EWORKSPACE is decided on the host from the pointer and the size alone, before any pointer is read and
+    before any HIP call: the device pointers passed here are made-up addresses that are never touched."""
+    from paper_2012_04930_amd import binding
+    L = binding.lib()
+    fake = lambda k: ctypes.c_void_p(0x10000000 + 0x100000 * k)      # 256-byte aligned, never dereferenced
+    need = ctypes.c_size_t()
+    n, nnz, f = 1000, 5000, 64
+    assert L.gcn_graph_workspace_bytes(n, nnz, f, 0, ctypes.byref(need)) == 0
+    out = ctypes.c_void_p(1)
+
+    def create(ws, ws_bytes):
+        return L.gcn_graph_create(ctypes.byref(out), n, nnz, fake(1), fake(2), fake(3), f, 0, fake(4), fake(5), 7,
+                                  ws, ctypes.c_size_t(ws_bytes), None)
+
+    for ws, ws_bytes, what in ((fake(6), need.value - 1, "one byte short"),
+                               (fake(6), 0, "empty"),
+                               (None, need.value, "missing"),
+                               (ctypes.c_void_p(0x10000000 + 0x600000 + 64), need.value + 4096, "misaligned")):
+        out.value = 1
+        assert create(ws, ws_bytes) == -4, what
+        assert out.value is None, what                               # a failed create leaves NULL behind
+        assert b"workspace" in L.gcn_last_error() and str(need.value).encode() in L.gcn_last_error()
+    # the subgraph approximation checks its workspace the same way
+    assert L.gcn_augment_workspace_bytes(n, ctypes.byref(need)) == 0
+    i64 = ctypes.c_int64
+    outs = [i64(), i64(), i64()]
+
+    def augment(ws, ws_bytes):
+        return L.gcn_augment_partition(i64(n), i64(nnz), fake(1), fake(2), fake(3), 5, 0, ctypes.c_double(0.1),
+                                       ctypes.c_uint64(1), ws, ctypes.c_size_t(ws_bytes), ctypes.byref(outs[0]),
+                                       ctypes.byref(outs[1]), ctypes.byref(outs[2]), fake(7), fake(8), fake(9), None)
+
+    assert augment(fake(6), need.value - 1) == -4
+    assert augment(ctypes.c_void_p(0x10000000 + 0x600000 + 128), need.value + 4096) == -4
+    assert augment(None, need.value) == -4

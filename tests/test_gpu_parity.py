@@ -19,6 +19,12 @@ def B():
     return binding
 
 
+def _say(capsys, text):
+    """Progress line that reaches the terminal even under output capture (long tests must not look hung)."""
+    with capsys.disabled():
+        print("\n    [%s] %s" % (time.strftime("%H:%M:%S"), text), end="", flush=True)
+
+
 def _heavy_row_workload(n=6000, heavy=(0, 17), seed=3):
     """Small random graph plus two vertices adjacent to almost everyone: rows longer than the
     in-LDS sort limit, so the bit-set path of the canonicalisation is exercised."""
@@ -103,6 +109,40 @@ def test_graph_errors_are_reported_not_raised_by_the_gpu(B):
     assert e.value.code == -1
     with pytest.raises(B.GcnError):
         B.gcn_model_create(g, [wl.dims[0] + 1, 4, wl.dims[-1]])
+    torch.cuda.synchronize()
+
+
+def test_workspaces_that_are_short_or_misaligned_are_refused(B):
+    """Every call that takes a workspace answers GCN_EWORKSPACE (-4) from the host, before a kernel runs, when the
+    workspace is one byte short, missing or not 256-byte aligned; a right-sized one is then accepted."""
+    import ctypes as C
+    wl = workloads.tiny(n=512)
+    g = H.gpu_graph(B, wl)
+    L = B.lib()
+    need = C.c_size_t()
+    st = torch.cuda.current_stream().cuda_stream
+    nl = len(wl.dims) - 1
+    dims = (C.c_int32 * (nl + 1))(*wl.dims)
+    assert L.gcn_model_workspace_bytes(g.handle, nl, dims, 0, C.byref(need)) == 0
+    ws = torch.empty(need.value + 512, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p()
+    for ptr, size in ((ws.data_ptr(), need.value - 1), (None, need.value), (ws.data_ptr() + 64, need.value)):
+        assert L.gcn_model_create(C.byref(h), g.handle, nl, dims, 0, 0.0, 0, ptr, size, st) == -4
+        assert h.value is None and b"workspace" in L.gcn_last_error()
+    assert L.gcn_model_create(C.byref(h), g.handle, nl, dims, 0, 0.0, 0, ws.data_ptr(), need.value, st) == 0
+    assert L.gcn_model_destroy(h) == 0
+    x = torch.zeros((wl.n, 24), device="cuda")
+    out = torch.empty_like(x)
+    assert L.gcn_aggregate_workspace_bytes(g.handle, 24, 0, C.byref(need)) == 0
+    ws = torch.empty(need.value + 512, dtype=torch.uint8, device="cuda")
+    for ptr, size in ((ws.data_ptr(), need.value - 1), (None, need.value), (ws.data_ptr() + 128, need.value)):
+        assert L.gcn_aggregate(g.handle, x.data_ptr(), out.data_ptr(), 24, 0, ptr, size, st) == -4
+    assert L.gcn_aggregate(g.handle, x.data_ptr(), out.data_ptr(), 24, 0, ws.data_ptr(), need.value, st) == 0
+    assert L.gcn_sage_workspace_bytes(g.handle, 16, 3, 2, 8, C.byref(need)) == 0
+    ws = torch.empty(need.value + 512, dtype=torch.uint8, device="cuda")
+    for ptr, size in ((ws.data_ptr(), need.value - 1), (None, need.value), (ws.data_ptr() + 64, need.value)):
+        assert L.gcn_sage_create(C.byref(h), g.handle, 16, 3, 2, 8, 0, ptr, size, st) == -4
+        assert h.value is None
     torch.cuda.synchronize()
 
 
@@ -243,7 +283,7 @@ def test_dropout_mask_and_scaling(B, oracle):
 
 
 # ------------------------------------------------------------------ full sizes, in the launch configuration bench.py times
-def test_benchmark_config_c3_full_size(B, oracle):
+def test_benchmark_config_c3_full_size(B, oracle, capsys):
     wl = workloads.reddit_partition()                  # 47,532 vertices, 23.7 M nonzeros, 602 -> 128 -> 41
     g = H.gpu_graph(B, wl)
     og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
@@ -252,32 +292,26 @@ def test_benchmark_config_c3_full_size(B, oracle):
     np.testing.assert_array_equal(col, og.col)
     np.testing.assert_array_equal(deg, og.deg)
     _, gpu = H.gpu_epoch(B, g, wl)
-    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c3: oracle " + t))
     H.compare_epoch(oracle, wl, gpu, tr, new)
 
 
-def test_benchmark_config_c3_full_size_in_bfloat16_storage(B, oracle):
+def test_benchmark_config_c3_full_size_in_bfloat16_storage(B, oracle, capsys):
     """The launch configuration `bench.py --dtype bf16` times: dense tiles on widened rows beside the gather."""
     wl = workloads.reddit_partition()
     g = H.gpu_graph(B, wl, dtype=B.GCN_BF16)
     assert B.gcn_graph_tile_info(g)["in_use"]
     _, gpu = H.gpu_epoch(B, g, wl, dtype=B.GCN_BF16, cache_ax=0)
-    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True, say=lambda t: _say(capsys, "c3 bf16: oracle " + t))
     H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
 
 
-def test_config_c2_full_size(B, oracle):
+def test_config_c2_full_size(B, oracle, capsys):
     wl = workloads.chung_lu_mid()                      # 100,000 vertices, light and heavy rows mixed
     g = H.gpu_graph(B, wl)
     _, gpu = H.gpu_epoch(B, g, wl)
-    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c2: oracle " + t))
     H.compare_epoch(oracle, wl, gpu, tr, new)
-
-
-def _say(capsys, text):
-    """Progress line that reaches the terminal even under output capture (long tests must not look hung)."""
-    with capsys.disabled():
-        print("\n    [%s] %s" % (time.strftime("%H:%M:%S"), text), end="", flush=True)
 
 
 @pytest.mark.timeout(900)
@@ -295,7 +329,7 @@ def test_config_c4_full_reddit_shape(B, oracle, capsys):
     _say(capsys, "c4: GPU epoch")
     _, gpu = H.gpu_epoch(B, g, wl)
     _say(capsys, "c4: oracle epoch")
-    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c4: oracle " + t))
     _say(capsys, "c4: comparing")
     H.compare_epoch(oracle, wl, gpu, tr, new)
 

@@ -53,6 +53,23 @@ class Case:
                           self.w2 if w2 is None else w2, batch, self.s1, self.s2, self.seed, step)
 
 
+def _oracle_backward(t, h1_gpu, w2, labels, s2):
+    """The oracle's backward pass on its own trace.  The ReLU decision is a yes/no taken by floating point: where the
+    GPU's activation disagrees with the oracle's pre-activation, that pre-activation must be ~0 (|Z1| < 1e-5) and
+    such entries must be rare; the test then turns the sign of exactly those entries in a copy of the oracle's own
+    Z1 (a change below the tolerance) and runs the unchanged oracle on it."""
+    flips = (np.asarray(h1_gpu) > 0) != (t.Z1 > 0)
+    n_flips = int(flips.sum())
+    print("ReLU decisions that differ: %d of %d" % (n_flips, flips.size))
+    assert np.abs(t.Z1[flips]).max(initial=0.0) < 1e-5
+    assert n_flips <= max(1, int(np.ceil(1e-5 * flips.size)))
+    if n_flips:
+        z = t.Z1.copy()
+        z[flips] = np.where(z[flips] > 0, -1.0, 1.0) * np.maximum(np.abs(z[flips]), np.finfo(np.float64).tiny)
+        t.Z1 = z
+    return SO.backward(t, w2, labels, s2)
+
+
 def _compare_forward(case, batch, step):
     got = case.gpu_forward(batch, step)
     t = case.oracle_forward(batch, step)
@@ -98,10 +115,7 @@ def test_gradients_and_adam_steps_follow_the_oracle(B, oracle):
         dw1 = B.gcn_sage_get_tensor(case.model, B.GCN_SAGE_DW1).cpu().numpy()
         dw2 = B.gcn_sage_get_tensor(case.model, B.GCN_SAGE_DW2).cpu().numpy()
         t = case.oracle_forward(batch, step, ws[0], ws[1])
-        # ReLU decisions from the GPU's activations; they may differ from the oracle's only where Z1 is ~0
-        flips = (got["H1"] > 0) != (t.Z1 > 0)
-        assert np.abs(t.Z1[flips]).max(initial=0.0) < 1e-5
-        ref_dw1, ref_dw2 = SO.backward(t, ws[1], wl.labels[batch], case.s2, gate=got["H1"])
+        ref_dw1, ref_dw2 = _oracle_backward(t, got["H1"], ws[1], wl.labels[batch], case.s2)
         ref_loss.append(t.loss)
         if step == 0:                                                               # same weights on both sides
             H.assert_close(dw1, ref_dw1, what="dW1")
@@ -145,7 +159,7 @@ def test_odd_shapes_and_degenerate_vertices(B, oracle, hidden, s1, s2, bsz):
     assert (got["inner"][one] == 17).all()
     B.gcn_sage_loss_acc(case.model, sync=False)
     B.gcn_sage_backward(case.model)
-    ref_dw1, ref_dw2 = SO.backward(t, case.w2.astype(np.float64), wl.labels[batch], s2, gate=got["H1"])
+    ref_dw1, ref_dw2 = _oracle_backward(t, got["H1"], case.w2.astype(np.float64), wl.labels[batch], s2)
     H.assert_close(B.gcn_sage_get_tensor(case.model, B.GCN_SAGE_DW1).cpu().numpy(), ref_dw1, what="dW1")
     H.assert_close(B.gcn_sage_get_tensor(case.model, B.GCN_SAGE_DW2).cpu().numpy(), ref_dw2, what="dW2")
 

@@ -346,6 +346,38 @@ def test_dropout_mask(oracle):
     np.testing.assert_allclose(tr_eval.H[1], np.maximum(tr_eval.Z[0], 0), rtol=0)
 
 
+@pytest.mark.parametrize("dims,p", [((8, 16, 3), 0.5), ((6, 7, 5, 3), 0.25)])
+def test_gradients_with_dropout_by_central_differences(oracle, dims, p):
+    """With the keep mask held fixed (same seed and epoch) the loss is a smooth function of the weights, and its
+    central differences must equal the backward pass: a missing or misplaced 1 / (1 - p) in the backward pass
+    (or a mask applied on one side only) changes dW of every layer below the last by that factor."""
+    a, rowptr, col, x, ws, labels, mask = _tiny_problem(n=40, dims=dims)
+    g = oracle.canonicalise(40, rowptr, col)
+    kw = dict(p=p, training=True, seed=11, epoch=3)
+    tr = oracle.backward(g, oracle.forward(g, x, ws, **kw), ws, labels, mask, p=p)
+    assert any((k == 0).any() for k in tr.keep) and any((k != 0).any() for k in tr.keep)
+
+    def loss_of(wlist):
+        return oracle.loss_acc(oracle.forward(g, x, wlist, **kw).Z[-1], labels, mask, want_grad=False)[0]
+
+    eps = 1e-5
+    for l in range(len(ws)):
+        num = np.zeros_like(ws[l])
+        for idx in np.ndindex(*ws[l].shape):
+            wp = [w.copy() for w in ws]
+            wm = [w.copy() for w in ws]
+            wp[l][idx] += eps
+            wm[l][idx] -= eps
+            num[idx] = (loss_of(wp) - loss_of(wm)) / (2 * eps)
+        err = np.abs(num - tr.dW[l]).max() / max(np.abs(num).max(), 1e-12)
+        assert err < 1e-6, (l, err)
+    # and the closed form of the step itself: dZ = dH * [Z > 0] * keep / (1 - p)
+    nl = len(ws)
+    for l in range(nl - 1, 0, -1):
+        dH = tr.G[l] @ ws[l].T
+        np.testing.assert_allclose(tr.dZ[l - 1], dH * (tr.Z[l - 1] > 0) * tr.keep[l - 1] / (1.0 - p), rtol=1e-13, atol=0)
+
+
 # ------------------------------------------------------------------ Adam (the paper's optimiser, Section 4.1)
 def test_adam_closed_forms(oracle):
     g = rng.normal_f32(3, 1, 60).reshape(12, 5).astype(np.float64)

@@ -165,8 +165,9 @@ def test_gradients_against_finite_differences():
                   (loss_of(p["W1"], Wp) - loss_of(p["W1"], Wm))
             num /= 2 * eps
             assert abs(num - dW[idx]) < 1e-7 * max(1.0, abs(num)), (which, idx, num, dW[idx])
-    # with every unit switched on (gate of ones) the pieces of dH are exactly the split of dC2
-    dW1g, _ = S.backward(t, p["W2"], p["labels"], p["S2"], gate=np.ones_like(t.Z1))
+    # with every unit switched on (all pre-activations positive) the pieces of dH are exactly the split of dC2
+    t.Z1 = np.abs(t.Z1) + 1.0
+    S.backward(t, p["W2"], p["labels"], p["S2"])
     B, S2 = len(p["batch"]), p["S2"]
     dH = t.dZ1.reshape(B, 1 + S2, hidden)
     np.testing.assert_allclose(dH[:, 0], dC2[:, :hidden], rtol=1e-13)
