@@ -135,6 +135,21 @@ int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, 
 int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *workspace,
                   size_t workspace_bytes, void *stream);
 
+/* gcn_aggregate for callers that cannot allocate device memory or size a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same result as gcn_aggregate (it runs
+ * the same kernels), but the scratch memory (the padded and scaled copy of `in`, the padded result, the tile
+ * product's sums and the chunk sums of split rows) is an array of GCN_STATIC_SCRATCH_BYTES bytes built into the
+ * library, one copy per GPU, held from the time the library is loaded on that GPU until the process ends.
+ * The call allocates nothing on the device (no hipMalloc, no hipFree, no event or stream is created).
+ *   - GCN_EWORKSPACE when gcn_aggregate_workspace_bytes(g, width, dtype) exceeds GCN_STATIC_SCRATCH_BYTES (about
+ *     (3 n + 2) x width rounded up to 16, x 4 bytes: e.g. 10,000 vertices at width 256, 57,000 at width 41);
+ *     use gcn_aggregate then.  GCN_EINVAL while kernel timing is enabled (timing creates events).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU race, whatever
+ *     streams and graphs they use.  Calls in stream order are fine; nothing is kept between calls.
+ * Asynchronous on `stream`. */
+#define GCN_STATIC_SCRATCH_BYTES (32u << 20)
+int gcn_aggregate_static(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Subgraph approximation: builds, on the GPU, the input the training step above runs on.
  *

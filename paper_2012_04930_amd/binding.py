@@ -23,7 +23,7 @@ STATUS = {0: "GCN_OK", -1: "GCN_EINVAL", -2: "GCN_EGRAPH", -3: "GCN_ELABEL", -4:
 
 EXPORTS = [
     "gcn_last_error", "gcn_graph_workspace_bytes", "gcn_graph_create", "gcn_graph_destroy", "gcn_graph_info",
-    "gcn_graph_get_csr", "gcn_graph_tile_info", "gcn_graph_get_tiles", "gcn_graph_get_masked_pattern", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_model_workspace_bytes",
+    "gcn_graph_get_csr", "gcn_graph_tile_info", "gcn_graph_get_tiles", "gcn_graph_get_masked_pattern", "gcn_aggregate_workspace_bytes", "gcn_aggregate", "gcn_aggregate_static", "gcn_model_workspace_bytes",
     "gcn_model_create", "gcn_model_destroy", "gcn_set_weights", "gcn_get_tensor", "gcn_forward", "gcn_loss_acc",
     "gcn_loss_acc_counts", "gcn_backward", "gcn_sgd_step", "gcn_timing_enable", "gcn_timing_reset", "gcn_timing_read",
     "gcn_calibration_copy", "gcn_set_tunable", "gcn_adam_step", "gcn_adam_update",
@@ -63,6 +63,7 @@ def lib():
         L.gcn_graph_get_masked_pattern.argtypes = [vp, vp, vp, C.POINTER(i64), vp]
         L.gcn_aggregate_workspace_bytes.argtypes = [vp, i32, C.c_int, C.POINTER(sz)]
         L.gcn_aggregate.argtypes = [vp, vp, vp, i32, C.c_int, vp, sz, vp]
+        L.gcn_aggregate_static.argtypes = [vp, vp, vp, i32, C.c_int, vp]
         L.gcn_model_workspace_bytes.argtypes = [vp, i32, C.POINTER(i32), C.c_int, C.POINTER(sz)]
         L.gcn_model_create.argtypes = [C.POINTER(vp), vp, i32, C.POINTER(i32), C.c_int, C.c_float, C.c_uint64, vp, sz,
                                        vp]
@@ -214,6 +215,17 @@ def gcn_aggregate(g: Graph, x: torch.Tensor, dtype: int = GCN_F32, ws: torch.Ten
     out = torch.empty_like(x)
     _check(L.gcn_aggregate(g.handle, _dev(x, torch.float32), out.data_ptr(), width, dtype, ws.data_ptr(), ws.numel(),
                            _stream()))
+    return out
+
+
+GCN_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def gcn_aggregate_static(g: Graph, x: torch.Tensor, out: torch.Tensor, dtype: int = GCN_F32) -> torch.Tensor:
+    """A_hat x into `out` (caller's tensors), with the library's built-in scratch array: nothing is allocated."""
+    assert x.shape[0] == g.n and out.shape == x.shape
+    _check(lib().gcn_aggregate_static(g.handle, _dev(x, torch.float32), _dev(out, torch.float32), x.shape[1], dtype,
+                                      _stream()))
     return out
 
 

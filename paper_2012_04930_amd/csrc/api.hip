@@ -70,6 +70,11 @@ void timing_begin(int width, hipStream_t st) {
     g_open_stop = ev.second;
 }
 
+bool timing_enabled() {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    return g_timing;
+}
+
 void timing_end(hipStream_t st) {
     std::lock_guard<std::mutex> lk(g_tmutex);
     if (g_open_stop) (void)hipEventRecord(g_open_stop, st);
@@ -642,6 +647,28 @@ int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, 
     return GCN_OK;
 }
 
+namespace {
+// The aggregation on its own, in a workspace of gcn_aggregate_workspace_bytes that the caller has checked.
+int aggregate_in(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *workspace,
+                 hipStream_t st) {
+    Carver c(workspace);
+    const int ld = padded_width(width);
+    float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
+    float *z = c.take<float>((size_t)(g->n + 1) * ld);
+    float *tile_sums = c.take<float>((size_t)g->n * ld);
+    float *chunk_sums = c.take<float>(chunk_sum_floats(g, ld));
+    const size_t es = dtype == GCN_BF16 ? 2 : 4;
+    int rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);
+    if (rc) return rc;
+    rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
+    if (rc) return rc;
+    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone, tile_sums, chunk_sums);
+    rc = spmm_launch(a, st);
+    if (rc) return rc;
+    return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
+}
+}  // namespace
+
 int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *workspace,
                   size_t workspace_bytes, void *stream) {
     size_t need = 0;
@@ -655,22 +682,69 @@ int gcn_aggregate(const gcn_graph *g, const float *in, float *out, int32_t width
         set_error("gcn_aggregate: workspace missing, misaligned or smaller than %zu bytes", need);
         return GCN_EWORKSPACE;
     }
-    hipStream_t st = (hipStream_t)stream;
-    Carver c(workspace);
-    const int ld = padded_width(width);
-    float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
-    float *z = c.take<float>((size_t)(g->n + 1) * ld);
-    float *tile_sums = c.take<float>((size_t)g->n * ld);
-    float *chunk_sums = c.take<float>(chunk_sum_floats(g, ld));
-    const size_t es = dtype == GCN_BF16 ? 2 : 4;
-    rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);
+    return aggregate_in(g, in, out, width, dtype, workspace, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------- gcn_aggregate_static
+// Scratch memory of gcn_aggregate_static.  Every GPU the library runs on holds its own copy of this array, at its
+// own address, from the moment the code object is loaded there until the process ends.  In host code the array's
+// name is only a stand-in for the symbol: the address a kernel may use comes from hipGetSymbolAddress, asked once
+// per device with that device current, and is what every launch and copy below is given.
+static __device__ __align__(256) unsigned char scratch[GCN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    GCN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("gcn_aggregate_static: device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+        return GCN_EINVAL;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("gcn_aggregate_static: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+            return GCN_EHIP;
+        }
+        if (!aligned256(p)) {
+            set_error("gcn_aggregate_static: the scratch array of device %d is not 256-byte aligned", dev);
+            return GCN_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return GCN_OK;
+}
+}  // namespace
+
+int gcn_aggregate_static(const gcn_graph *g, const float *in, float *out, int32_t width, int dtype, void *stream) {
+    size_t need = 0;
+    int rc = gcn_aggregate_workspace_bytes(g, width, dtype, &need);
     if (rc) return rc;
-    rc = fill_zero((char *)t + (size_t)g->n * ld * es, (size_t)ld * es, st);
+    if (!in || !out) {
+        set_error("gcn_aggregate_static: null pointer");
+        return GCN_EINVAL;
+    }
+    if (need > (size_t)GCN_STATIC_SCRATCH_BYTES) {
+        set_error("gcn_aggregate_static: this graph and width need %zu bytes of scratch memory, the built-in array has %zu; "
+                  "use gcn_aggregate with a workspace of the caller's",
+                  need, (size_t)GCN_STATIC_SCRATCH_BYTES);
+        return GCN_EWORKSPACE;
+    }
+    if (timing_enabled()) {
+        set_error("gcn_aggregate_static: kernel timing is on (it creates events); switch it off first");
+        return GCN_EINVAL;
+    }
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
     if (rc) return rc;
-    SpmmArgs a = spmm_args(g, t, dtype, ld, z, GCN_F32, ld, ld, width, kEpiNone, tile_sums, chunk_sums);
-    rc = spmm_launch(a, st);
-    if (rc) return rc;
-    return unpad_rows(z, GCN_F32, ld, g->n, width, out, nullptr, st);
+    return aggregate_in(g, in, out, width, dtype, ws, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------------------------------- subgraph approximation

@@ -289,5 +289,6 @@ int gemm_bf16_tn_partials(const void *a, int lda, const void *b, int ldb, int ld
 // Event timing of aggregation launches (api.hip)
 void timing_begin(int width, hipStream_t st);
 void timing_end(hipStream_t st);
+bool timing_enabled();
 
 }  // namespace gcn
