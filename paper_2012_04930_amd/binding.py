@@ -176,14 +176,17 @@ def gcn_graph_tile_info(g: Graph) -> dict:
     return {"n_tiles": nt.value, "nnz_dense": nd.value, "in_use": bool(use.value)}
 
 
+TILE_ROWS = 128     # a dense tile covers 128 rows by 32 columns
+
+
 def gcn_graph_get_tiles(g: Graph):
-    """-> (tile_ptr, tile_col, bits [n_tiles x 32], res_rowptr, res_col)"""
+    """-> (tile_ptr, tile_col, bits [n_tiles x 128], res_rowptr, res_col)"""
     info = gcn_graph_info(g)
     ti = gcn_graph_tile_info(g)
     res_nnz = info["nnz"] - ti["nnz_dense"]
-    tile_ptr = torch.empty((info["n"] + 31) // 32 + 1, dtype=torch.int64, device="cuda")
+    tile_ptr = torch.empty((info["n"] + TILE_ROWS - 1) // TILE_ROWS + 1, dtype=torch.int64, device="cuda")
     tile_col = torch.empty(ti["n_tiles"], dtype=torch.int32, device="cuda")
-    bits = torch.empty((ti["n_tiles"], 32), dtype=torch.int32, device="cuda")
+    bits = torch.empty((ti["n_tiles"], TILE_ROWS), dtype=torch.int32, device="cuda")
     res_rowptr = torch.empty(info["n"] + 1, dtype=torch.int64, device="cuda")
     res_col = torch.empty(max(res_nnz, 1), dtype=torch.int32, device="cuda")
     got = C.c_int64()

@@ -137,6 +137,11 @@ uint64_t host_mix64(uint64_t z) {
 
 bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
+// floats of the tile product's buffer for one aggregation of `cols` columns: the n x cols sums, then the partial sums
+size_t tile_sum_floats(const gcn_graph *g, int cols) {
+    return ((size_t)g->n + (size_t)g->tiles.n_slots * kTileRows) * (size_t)cols;
+}
+
 // floats for the chunk sums of one aggregation of `cols` columns over either form of the pattern
 size_t chunk_sum_floats(const gcn_graph *g, int cols) {
     int64_t chunks = g->rows.n_chunks > g->res_rows.n_chunks ? g->rows.n_chunks : g->res_rows.n_chunks;
@@ -144,7 +149,8 @@ size_t chunk_sum_floats(const gcn_graph *g, int cols) {
     return (size_t)chunks * (size_t)cols;
 }
 
-// tile_sums: n x cols floats for the tile product when it runs beside the gather kernel (null: one after the other);
+// tile_sums: tile_sum_floats(g, cols) floats for the tile product (its output when it runs beside the gather kernel,
+// and the partial sums of row blocks whose tiles were cut into runs);
 // gather_sums: the same again for the gather kernel's plain sums when the output is bfloat16 (else null)
 SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, void *out, int out_dtype, int ld_out,
                    int cols, int width, int epilogue, float *tile_sums, float *chunk_sums,
@@ -185,7 +191,13 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
         a.tile_ptr = g->tiles.tile_ptr;
         a.tile_col = g->tiles.tile_col;
         a.bits = g->tiles.bits;
-        a.n_rt = g->tiles.n_rt;
+        a.tile_items = g->tiles.items;
+        a.n_items = g->tiles.n_items;
+        a.tile_folds = g->tiles.folds;
+        a.n_folds = g->tiles.n_folds;
+        a.n_slots = g->tiles.n_slots;
+        // the partial sums of row blocks whose tiles were cut into runs follow the n x cols sums in the same buffer
+        a.tile_partial = tile_sums ? tile_sums + (size_t)g->n * cols : nullptr;
         if (tile_sums && g->side) {
             a.gather_sums = gather_sums;
             a.tile_sums = tile_sums;
@@ -234,14 +246,17 @@ void carve_graph(Carver &c, gcn_graph &g) {
     g.pb.blocksum = c.take<int64_t>(scan_blocks(n > g.pb.split_cap ? n : g.pb.split_cap));
     g.pb.flags = c.take<int32_t>(16);
     TileBuffers &tb = g.tiles;
-    tb.n_rt = (n + 31) / 32;
+    tb.n_rb = (n + kTileRows - 1) / kTileRows;
     tb.capacity = (int64_t)tiles_capacity(cap);
-    tb.tile_cnt = c.take<int32_t>(tb.n_rt);
-    tb.tile_ptr = c.take<int64_t>(tb.n_rt + 1);
+    tb.tile_cnt = c.take<int32_t>(tb.n_rb);
+    tb.tile_ptr = c.take<int64_t>(tb.n_rb + 1);
     tb.tile_col = c.take<int32_t>(tb.capacity);
     tb.tile_rt = c.take<int32_t>(tb.capacity);
-    tb.bits = c.take<uint32_t>((size_t)tb.capacity * 32);
+    tb.bits = c.take<uint32_t>((size_t)tb.capacity * kTileRows);
     tb.totals = c.take<unsigned long long>(2);
+    tb.item_capacity = tiles_item_capacity(tb.n_rb, tb.capacity);
+    tb.items = c.take<int32_t>(tb.item_capacity * 4);
+    tb.folds = c.take<int32_t>((size_t)tb.n_rb * 4);
     g.res = g.pb;   // shares dinv and the creation-time scratch arrays; its own pattern and schedule follow
     g.res.rowptr = c.take<int64_t>(n + 1);
     g.res.col = c.take<int32_t>(cap + kColSlack);
@@ -308,7 +323,7 @@ void carve_model(Carver &c, gcn_model &m) {
         const int slab = slab_max < m.g->ldf ? slab_max : m.g->ldf;
         widest = slab > widest ? slab : widest;
     }
-    m.tile_sums = m.g->use_tiles ? c.take<float>((size_t)n * widest) : nullptr;
+    m.tile_sums = m.g->use_tiles ? c.take<float>(tile_sum_floats(m.g, widest)) : nullptr;
     m.gather_sums = (m.g->use_tiles && m.dtype == GCN_BF16) ? c.take<float>((size_t)n * widest) : nullptr;
     m.chunk_sums = c.take<float>(chunk_sum_floats(m.g, widest));
     m.partial_floats = pf;
@@ -490,16 +505,16 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
     };
     HIP_OR_FAIL(read_classes(g->pb, flags, g->rows));
 
-    // Dense tiles: select, then decide.  Knobs read here: "tile_min_entries" (default 128 of 1024), "spmm_tiles"
+    // Dense tiles: select, then decide.  Knobs read here: "tile_min_entries" (default kTileMinEntriesDefault of the 4096 places of a tile), "spmm_tiles"
     // (-1: use the tiles when they hold at least a quarter of the entries, 0: never build, 1: whenever there is one).
     const int64_t tiles_knob = tunable("spmm_tiles", -1);
     if (tiles_knob != 0) {
-        int64_t me = tunable("tile_min_entries", 128);
+        int64_t me = tunable("tile_min_entries", kTileMinEntriesDefault);
         if (me < kTileMinEntriesFloor) me = kTileMinEntriesFloor;
-        if (me > 1024) me = 1024;
+        if (me > kTileRows * 32) me = kTileRows * 32;
         FAIL_IF(tiles_select(n, g->pb.rowptr, g->pb.col, (int)me, g->tiles, g->pb.blocksum, st));
         unsigned long long dense = 0;
-        HIP_OR_FAIL(hipMemcpyAsync(&g->n_tiles, g->tiles.tile_ptr + g->tiles.n_rt, sizeof(int64_t),
+        HIP_OR_FAIL(hipMemcpyAsync(&g->n_tiles, g->tiles.tile_ptr + g->tiles.n_rb, sizeof(int64_t),
                                    hipMemcpyDeviceToHost, st));
         HIP_OR_FAIL(hipMemcpyAsync(&dense, g->tiles.totals, sizeof(dense), hipMemcpyDeviceToHost, st));
         HIP_OR_FAIL(hipStreamSynchronize(st));
@@ -512,6 +527,11 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         g->use_tiles = g->n_tiles > 0 && (tiles_knob > 0 || g->nnz_dense * 4 >= g->E);
         if (g->use_tiles) {
             FAIL_IF(tiles_build(n, g->pb.rowptr, g->pb.col, g->n_tiles, g->tiles, g->res, st));
+            std::vector<int64_t> tile_ptr((size_t)g->tiles.n_rb + 1);
+            HIP_OR_FAIL(hipMemcpyAsync(tile_ptr.data(), g->tiles.tile_ptr, tile_ptr.size() * sizeof(int64_t),
+                                       hipMemcpyDeviceToHost, st));
+            HIP_OR_FAIL(hipStreamSynchronize(st));
+            FAIL_IF(tiles_plan(tile_ptr, g->tiles, st));
             FAIL_IF(fill_zero(g->res.flags, 16 * sizeof(int32_t), st));
             FAIL_IF(prep_schedule(n, g->res, st));
             HIP_OR_FAIL(hipMemcpyAsync(flags, g->res.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
@@ -605,12 +625,13 @@ int gcn_graph_get_tiles(const gcn_graph *g, int64_t *tile_ptr, int32_t *tile_col
     const int64_t res_E = g->E - g->nnz_dense;
     if (res_nnz) *res_nnz = res_E;
     if (tile_ptr)
-        GCN_HIP(hipMemcpyAsync(tile_ptr, g->tiles.tile_ptr, (g->tiles.n_rt + 1) * sizeof(int64_t),
+        GCN_HIP(hipMemcpyAsync(tile_ptr, g->tiles.tile_ptr, (g->tiles.n_rb + 1) * sizeof(int64_t),
                                hipMemcpyDeviceToDevice, st));
     if (tile_col)
         GCN_HIP(hipMemcpyAsync(tile_col, g->tiles.tile_col, g->n_tiles * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     if (bits)
-        GCN_HIP(hipMemcpyAsync(bits, g->tiles.bits, g->n_tiles * 32 * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+        GCN_HIP(hipMemcpyAsync(bits, g->tiles.bits, g->n_tiles * kTileRows * sizeof(uint32_t), hipMemcpyDeviceToDevice,
+                               st));
     if (res_rowptr)
         GCN_HIP(hipMemcpyAsync(res_rowptr, g->res.rowptr, (g->n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
     if (res_col && res_E > 0)
@@ -641,7 +662,7 @@ int gcn_aggregate_workspace_bytes(const gcn_graph *g, int32_t width, int dtype, 
     const int ld = padded_width(width);
     c.take<float>((size_t)(g->n + 1) * ld);
     c.take<float>((size_t)(g->n + 1) * ld);
-    c.take<float>((size_t)g->n * ld);
+    c.take<float>(tile_sum_floats(g, ld));
     c.take<float>(chunk_sum_floats(g, ld));
     *bytes = c.bytes();
     return GCN_OK;
@@ -655,7 +676,7 @@ int aggregate_in(const gcn_graph *g, const float *in, float *out, int32_t width,
     const int ld = padded_width(width);
     float *t = c.take<float>((size_t)(g->n + 1) * ld);     // holds float or bfloat16 rows
     float *z = c.take<float>((size_t)(g->n + 1) * ld);
-    float *tile_sums = c.take<float>((size_t)g->n * ld);
+    float *tile_sums = c.take<float>(tile_sum_floats(g, ld));
     float *chunk_sums = c.take<float>(chunk_sum_floats(g, ld));
     const size_t es = dtype == GCN_BF16 ? 2 : 4;
     int rc = pad_rows(in, g->n, width, t, dtype, ld, g->pb.dinv, st);

@@ -45,7 +45,10 @@ constexpr int kChunk = 2048;       // entries per chunk of a split row
 constexpr int kXcds = 8;       // workgroup ids are dealt round-robin to 8 XCDs, each with its own L2
 constexpr int kRangesPerXcd = 2;  // column ranges of the phased aggregation schedule per XCD
 constexpr int kColBlocks = kXcds * kRangesPerXcd;
-constexpr int kTileMinEntriesFloor = 64;   // a dense 32 x 32 tile holds at least this many entries (bounds their number)
+constexpr int kTileRows = 128;             // a dense tile covers this many rows by 32 columns
+constexpr int kTileMinEntriesFloor = 64;   // a dense tile holds at least this many entries (bounds their number)
+constexpr int kTileMinEntriesDefault = 64; // the break-even of one tile product against gathering its entries
+constexpr int kTileRunMin = 32;            // a row block's tiles are cut into runs no shorter than this
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int padded_width(int w) { return (int)round_up(w, kLdAlign); }
@@ -123,24 +126,32 @@ inline bool phased_shape(int64_t max_rows_per_xcd, int *W, int *R) {
 int prep_balance_rows(int64_t n, const int32_t *deg, const int32_t *row_start, int W, int R, int32_t *prow,
                       hipStream_t st);
 // ---------------------------------------------------------------------------------------------
-// Dense 32 x 32 tiles of the adjacency pattern (tiles.hip)
+// Dense tiles (kTileRows x 32) of the adjacency pattern (tiles.hip)
 struct TileBuffers {
-    int64_t n_rt = 0;       // row tiles = column tiles = ceil(n / 32)
+    int64_t n_rb = 0;       // row blocks = ceil(n / kTileRows)
     int64_t capacity = 0;   // dense tiles the arrays can hold
-    int32_t *tile_cnt = nullptr;   // n_rt: dense tiles of each row tile
-    int64_t *tile_ptr = nullptr;   // n_rt + 1: exclusive prefix of tile_cnt
-    int32_t *tile_col = nullptr;   // capacity: column tile of each dense tile, ascending inside a row tile
-    int32_t *tile_rt = nullptr;    // capacity: row tile of each dense tile
-    uint32_t *bits = nullptr;      // capacity * 32: word r of tile k = columns that row r of the tile holds
+    int32_t *tile_cnt = nullptr;   // n_rb: dense tiles of each row block
+    int64_t *tile_ptr = nullptr;   // n_rb + 1: exclusive prefix of tile_cnt
+    int32_t *tile_col = nullptr;   // capacity: column tile (32 columns) of each dense tile, ascending inside a row block
+    int32_t *tile_rt = nullptr;    // capacity: row block of each dense tile
+    uint32_t *bits = nullptr;      // capacity * kTileRows: word r of tile k = columns that row r of the tile holds
     unsigned long long *totals = nullptr;   // [0] stored entries inside the dense tiles
+    // the product's work items (runs of tiles of one row block) and the row blocks whose runs must be added up
+    size_t item_capacity = 0;
+    void *items = nullptr;         // item_capacity x 4 int32
+    void *folds = nullptr;         // n_rb x 4 int32
+    int32_t n_items = 0, n_folds = 0, n_slots = 0;   // n_slots: blocks of kTileRows rows in the partial-sum buffer
 };
 size_t tiles_capacity(int64_t entries);
+size_t tiles_item_capacity(int64_t n_rb, int64_t tile_capacity);
 // fills tile_cnt, tile_ptr, tile_col, tile_rt and totals from the canonical pattern
 int tiles_select(int64_t n, const int64_t *rowptr, const int32_t *col, int min_entries, TileBuffers &tb,
                  int64_t *blocksum, hipStream_t st);
 // fills bits, and res.deg / res.rowptr / res.col with the entries outside the dense tiles
 int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_tiles, TileBuffers &tb,
                 PrepBuffers &res, hipStream_t st);
+// fills items / folds and their counts from a host copy of tile_ptr (synchronous)
+int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_t st);
 
 int prep_labels_mask(int64_t n, const int32_t *labels, const uint8_t *mask, int32_t n_classes, int32_t *labels_out,
                      uint8_t *mask_out, int32_t *flags, hipStream_t st);
@@ -233,7 +244,11 @@ struct SpmmArgs {
     const int64_t *tile_ptr;
     const int32_t *tile_col;
     const uint32_t *bits;
-    int64_t n_rt;
+    const void *tile_items;   // work items of the tile product and their number
+    int32_t n_items;
+    const void *tile_folds;   // row blocks whose runs are added up afterwards
+    int32_t n_folds, n_slots;
+    float *tile_partial;      // n_slots x kTileRows x (leading dimension of the tile product's output) floats
     // Overlap of the two parts (all four set, or none): the tile product runs on `side` into tile_sums [n x cols
     // floats] while the gather kernel writes plain sums to out on the caller's stream; a third launch adds the two
     // and finishes the rows.  Without them the gather kernel follows the tile product and finishes the rows itself.
@@ -249,9 +264,8 @@ enum SpmmFinish {
     kFinishAddStored = 1,  // first add what the output already holds (the tiles' sums), then as above
     kFinishPlainSum = 2    // store the plain sum (float32 output); a later launch finishes the rows
 };
-// dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling); beside_gather: the launch shares the
-// chip with the gather kernel
-int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, bool beside_gather, hipStream_t st);
+// dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling)
+int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------

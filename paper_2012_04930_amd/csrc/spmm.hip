@@ -589,7 +589,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         // fork: the tile product on the side stream, the gather over the residual entries on the caller's
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
         if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");
-        if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, true, a.side);
+        if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, a.side);
         if (rc == GCN_OK) rc = hip_status(hipEventRecord(a.ev_join, a.side), "hipEventRecord");
         b.finish_mode = kFinishPlainSum;
         if (a.out_dtype != GCN_F32) {
@@ -598,7 +598,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
             b.ld_out = a.cols;
         }
     } else if (a.tile_ptr) {
-        rc = tiles_launch(a, static_cast<float *>(a.out), a.ld_out, false, st);
+        rc = tiles_launch(a, static_cast<float *>(a.out), a.ld_out, st);
         b.finish_mode = kFinishAddStored;
     }
     if (rc == GCN_OK) {

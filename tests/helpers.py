@@ -201,22 +201,27 @@ def compare_epoch(O, wl, gpu, tr, new_w, rtol=RTOL_F32):
         assert_close(gpu["W"][l - 1], ref_w[l - 1], rtol, "W%d after SGD" % l)
 
 
+TILE_ROWS = 128     # a dense tile covers 128 rows by 32 columns
+
+
 def tile_split(n, rowptr, col, min_entries):
-    """The definition: count the stored entries of every aligned 32 x 32 tile of the canonical pattern; tiles with at
-    least min_entries are dense.  -> tile_ptr, tile_col, bits [n_tiles x 32] (uint32), res_rowptr, res_col"""
+    """The definition: count the stored entries of every aligned tile of 128 rows x 32 columns of the canonical
+    pattern; tiles with at least min_entries are dense.
+    -> tile_ptr (per block of 128 rows), tile_col, bits [n_tiles x 128] (uint32), res_rowptr, res_col, entries in tiles"""
     rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
-    n_rt = (n + 31) // 32
-    key = (rows // 32) * n_rt + col // 32
+    n_rb = (n + TILE_ROWS - 1) // TILE_ROWS
+    n_ct = (n + 31) // 32
+    key = (rows // TILE_ROWS) * n_ct + col // 32
     uniq, inverse, cnt = np.unique(key, return_inverse=True, return_counts=True)
     dense = cnt >= min_entries
-    dkeys = uniq[dense]                                     # ascending: by row tile, then column tile
-    tile_ptr = np.zeros(n_rt + 1, dtype=np.int64)
-    np.cumsum(np.bincount(dkeys // n_rt, minlength=n_rt), out=tile_ptr[1:])
-    tile_col = (dkeys % n_rt).astype(np.int32)
+    dkeys = uniq[dense]                                     # ascending: by row block, then column tile
+    tile_ptr = np.zeros(n_rb + 1, dtype=np.int64)
+    np.cumsum(np.bincount(dkeys // n_ct, minlength=n_rb), out=tile_ptr[1:])
+    tile_col = (dkeys % n_ct).astype(np.int32)
     in_dense = dense[inverse]
     tile_of_entry = np.cumsum(dense)[inverse] - 1            # index among the dense tiles
-    bits = np.zeros((len(dkeys), 32), dtype=np.uint32)
-    np.bitwise_or.at(bits, (tile_of_entry[in_dense], rows[in_dense] % 32),
+    bits = np.zeros((len(dkeys), TILE_ROWS), dtype=np.uint32)
+    np.bitwise_or.at(bits, (tile_of_entry[in_dense], rows[in_dense] % TILE_ROWS),
                      (np.uint32(1) << (col[in_dense] % 32).astype(np.uint32)))
     res_rowptr = np.zeros(n + 1, dtype=np.int64)
     np.cumsum(np.bincount(rows[~in_dense], minlength=n), out=res_rowptr[1:])

@@ -1,5 +1,6 @@
-"""Dense 32 x 32 tiles of the adjacency pattern: the split of the pattern is integer work and is compared bit by
-bit with a numpy restatement of its definition; the aggregation that uses it is compared with the oracle."""
+"""Dense tiles (128 rows x 32 columns) of the adjacency pattern: the split of the pattern is integer work and is
+compared bit by bit with a numpy restatement of its definition; the aggregation that uses it (three bfloat16
+matrix-core passes over an exact split of the float32 rows) is compared with the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -27,7 +28,7 @@ def knobs(B):
         touched.append(name)
         B.gcn_set_tunable(name, value)
     yield set_
-    defaults = {"spmm_tiles": -1, "tile_min_entries": 128, "spmm_phased": -1, "spmm_overlap": 1, "spmm_masked": 1}
+    defaults = {"spmm_tiles": -1, "tile_min_entries": 64, "spmm_phased": -1, "spmm_overlap": 1, "spmm_masked": 1}
     for name in touched:
         B.gcn_set_tunable(name, defaults[name])
 
@@ -45,8 +46,8 @@ def _complete_blocks(n, block):
 
 def _cases():
     yield "partition_2.4k", workloads.reddit_partition(scale=0.05), 64
-    yield "partition_4.7k_thr128", workloads.reddit_partition(scale=0.1), 128
-    wl = workloads.tiny(n=331)                 # 331 = 10 * 32 + 11: ragged last tile, cliques of 96 and a last of 43
+    yield "partition_4.7k_thr400", workloads.reddit_partition(scale=0.1), 400
+    wl = workloads.tiny(n=331)                 # 331 = 2 * 128 + 75 = 10 * 32 + 11: ragged last tiles both ways; cliques of 96 and a last of 43
     wl.rowptr, wl.col = _complete_blocks(331, 96)
     yield "cliques_331", wl, 64
 
@@ -75,12 +76,12 @@ def test_tile_split_is_bit_exact(B, oracle, knobs, case):
 
 def test_all_entries_dense_leaves_an_empty_residual(B, oracle, knobs):
     wl = workloads.tiny(n=256)
-    wl.rowptr, wl.col = _complete_blocks(256, 64)        # 4 cliques of 64: 16 full tiles, nothing else
+    wl.rowptr, wl.col = _complete_blocks(256, 64)        # 4 cliques of 64: two row blocks with 4 half-full tiles each
     knobs("spmm_tiles", 1)
-    knobs("tile_min_entries", 1024)
+    knobs("tile_min_entries", 2048)
     g = H.gpu_graph(B, wl)
     info = B.gcn_graph_tile_info(g)
-    assert info == {"n_tiles": 16, "nnz_dense": 256 * 64, "in_use": True}
+    assert info == {"n_tiles": 8, "nnz_dense": 256 * 64, "in_use": True}
     og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
     x = rng.normal_f32(5, 1, wl.n * 40).reshape(wl.n, 40)
     got = B.gcn_aggregate(g, torch.from_numpy(x).cuda()).cpu().numpy()
@@ -122,6 +123,43 @@ def test_aggregate_with_tiles_matches_oracle(B, oracle, knobs, case, width):
     seq16 = B.gcn_aggregate(g, xd, dtype=B.GCN_BF16).cpu().numpy()
     knobs("spmm_overlap", 1)
     np.testing.assert_array_equal(seq16, plain16)
+
+
+def _hub_graph(n=6000, hubs=(0, 17, 40), seed=3):
+    """A sparse random graph plus three vertices adjacent to nine tenths of all others: the row block that holds them
+    has a dense tile in every column tile (3 x 32 x 0.9 entries each), far more than any other block."""
+    rowptr, col = graphs.erdos_renyi_gnm(n, 3 * n, seed)
+    u = [np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))]
+    v = [col.astype(np.int64)]
+    for hv in hubs:
+        others = np.nonzero(rng.uniform(seed, 50 + hv, n) < 0.9)[0]
+        u.append(np.full(others.size, hv, dtype=np.int64))
+        v.append(others)
+    return graphs.pairs_to_csr(n, np.concatenate(u), np.concatenate(v))
+
+
+@pytest.mark.parametrize("width,bf", [(128, False), (41, False), (200, False), (64, True)])
+def test_row_block_with_many_tiles_is_cut_into_runs(B, oracle, knobs, width, bf):
+    """The hubs' row block holds 188 dense tiles, the others one or two: its tiles are cut into runs that several
+    workgroups take, and the runs' partial sums are added in run order."""
+    wl = workloads.tiny(n=6000)
+    wl.rowptr, wl.col = _hub_graph()
+    knobs("spmm_tiles", 1)
+    g = H.gpu_graph(B, wl)
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    tile_ptr = H.tile_split(wl.n, og.rowptr, og.col, 64)[0]
+    per_block = np.diff(tile_ptr)
+    assert per_block[0] > 150 and np.sort(per_block)[-2] < 10
+    x = rng.normal_f32(width, 9, wl.n * width).reshape(wl.n, width)
+    xd = torch.from_numpy(x).cuda()
+    dtype = B.GCN_BF16 if bf else B.GCN_F32
+    ref = oracle.aggregate(og, x)
+    for overlap in ((1,) if bf else (1, 0)):
+        knobs("spmm_overlap", overlap)
+        runs = [B.gcn_aggregate(g, xd, dtype=dtype).cpu().numpy() for _ in range(3)]
+        H.assert_close(runs[0], ref, rtol=H.RTOL_BF16 if bf else H.RTOL_F32, what="runs, overlap %d" % overlap)
+        for r in runs[1:]:
+            np.testing.assert_array_equal(r, runs[0])
 
 
 @pytest.mark.parametrize("width", [41, 128, 256])
@@ -195,7 +233,7 @@ def test_full_step_with_and_without_the_masked_pattern(B, oracle, knobs, dtype_n
 def test_automatic_choice(B, knobs):
     """Default rule: tiles in use when they hold at least a quarter of the entries."""
     dense = H.gpu_graph(B, workloads.reddit_partition(scale=0.1))
-    sparse = H.gpu_graph(B, workloads.chung_lu_mid(scale=0.05))
+    sparse = H.gpu_graph(B, workloads.chung_lu_mid(scale=0.4))     # communities of 2,000 vertices at degree 20: under 1 % full
     assert B.gcn_graph_tile_info(dense)["in_use"]
     info = B.gcn_graph_tile_info(sparse)
     assert not info["in_use"] and info["nnz_dense"] * 4 < B.gcn_graph_info(sparse)["nnz"]
