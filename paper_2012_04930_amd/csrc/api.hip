@@ -137,9 +137,15 @@ uint64_t host_mix64(uint64_t z) {
 
 bool aligned256(const void *p) { return ((uintptr_t)p & 255u) == 0; }
 
-// floats of the tile product's buffer for one aggregation of `cols` columns: the n x cols sums, then the partial sums
+// floats of the tile product's buffer for one aggregation of `cols` columns: the n x cols sums, then the partial
+// sums (blocks of kTileRows x cols), then the input split into bfloat16 planes (sized for float32 input, the larger case)
+size_t tile_partial_offset(const gcn_graph *g, int cols) { return (size_t)g->n * (size_t)cols; }
+size_t tile_planes_offset(const gcn_graph *g, int cols) {
+    const size_t floats = ((size_t)g->n + (size_t)g->tiles.n_slots * kTileRows) * (size_t)cols;
+    return (floats + 63) & ~(size_t)63;   // 256-byte aligned when the buffer is
+}
 size_t tile_sum_floats(const gcn_graph *g, int cols) {
-    return ((size_t)g->n + (size_t)g->tiles.n_slots * kTileRows) * (size_t)cols;
+    return tile_planes_offset(g, cols) + tiles_plane_bytes(g->n, cols, GCN_F32) / sizeof(float);
 }
 
 // floats for the chunk sums of one aggregation of `cols` columns over either form of the pattern
@@ -197,7 +203,9 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
         a.n_folds = g->tiles.n_folds;
         a.n_slots = g->tiles.n_slots;
         // the partial sums of row blocks whose tiles were cut into runs follow the n x cols sums in the same buffer
-        a.tile_partial = tile_sums ? tile_sums + (size_t)g->n * cols : nullptr;
+        // (the buffer was sized for the widest aggregation, so this one's parts fit)
+        a.tile_partial = tile_sums ? tile_sums + tile_partial_offset(g, cols) : nullptr;
+        a.tile_planes = tile_sums ? tile_sums + tile_planes_offset(g, cols) : nullptr;
         if (tile_sums && g->side) {
             a.gather_sums = gather_sums;
             a.tile_sums = tile_sums;

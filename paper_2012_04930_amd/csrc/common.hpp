@@ -48,7 +48,8 @@ constexpr int kColBlocks = kXcds * kRangesPerXcd;
 constexpr int kTileRows = 128;             // a dense tile covers this many rows by 32 columns
 constexpr int kTileMinEntriesFloor = 64;   // a dense tile holds at least this many entries (bounds their number)
 constexpr int kTileMinEntriesDefault = 64; // the break-even of one tile product against gathering its entries
-constexpr int kTileRunMin = 32;            // a row block's tiles are cut into runs no shorter than this
+constexpr int kTileRunMin = 32;            // a row block with up to 1.5 x this many tiles is never cut into runs
+constexpr int kTileChunkMin = 8;           // runs are no shorter than this
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int padded_width(int w) { return (int)round_up(w, kLdAlign); }
@@ -248,7 +249,8 @@ struct SpmmArgs {
     int32_t n_items;
     const void *tile_folds;   // row blocks whose runs are added up afterwards
     int32_t n_folds, n_slots;
-    float *tile_partial;      // n_slots x kTileRows x (leading dimension of the tile product's output) floats
+    float *tile_partial;      // n_slots x kTileRows x cols floats
+    void *tile_planes;        // tiles_plane_bytes(n, cols, t_dtype): the input split and reordered for the matrix cores
     // Overlap of the two parts (all four set, or none): the tile product runs on `side` into tile_sums [n x cols
     // floats] while the gather kernel writes plain sums to out on the caller's stream; a third launch adds the two
     // and finishes the rows.  Without them the gather kernel follows the tile product and finishes the rows itself.
@@ -264,6 +266,7 @@ enum SpmmFinish {
     kFinishAddStored = 1,  // first add what the output already holds (the tiles' sums), then as above
     kFinishPlainSum = 2    // store the plain sum (float32 output); a later launch finishes the rows
 };
+size_t tiles_plane_bytes(int64_t n, int cols, int dtype);
 // dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling)
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);

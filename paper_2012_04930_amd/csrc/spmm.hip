@@ -585,12 +585,19 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         timing_end(st);
         return GCN_EINVAL;
     }
+    // Side by side: the tile product on the side stream, the gather over the residual entries on the caller's (knob
+    // "spmm_tiles_first": the other way round; measured the same on the benchmark partition, where both kernels
+    // slow each other down through the bytes they pull from the L2s: 254 us together against 195 + 98 us alone).
+    hipStream_t gather_stream = st;
     if (a.tile_ptr && overlap) {
-        // fork: the tile product on the side stream, the gather over the residual entries on the caller's
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
         if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");
-        if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, a.side);
-        if (rc == GCN_OK) rc = hip_status(hipEventRecord(a.ev_join, a.side), "hipEventRecord");
+        if (rc == GCN_OK && tunable("spmm_tiles_first", 0) != 0) {
+            rc = tiles_launch(a, a.tile_sums, a.cols, st);
+            gather_stream = a.side;
+        } else if (rc == GCN_OK) {
+            rc = tiles_launch(a, a.tile_sums, a.cols, a.side);
+        }
         b.finish_mode = kFinishPlainSum;
         if (a.out_dtype != GCN_F32) {
             b.out = a.gather_sums;
@@ -602,13 +609,14 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         b.finish_mode = kFinishAddStored;
     }
     if (rc == GCN_OK) {
-        if (b.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, st);
-        else if (b.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, st);
-        else rc = launch_by_width<bf16_t, bf16_t>(b, st);
+        if (b.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, gather_stream);
+        else if (b.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, gather_stream);
+        else rc = launch_by_width<bf16_t, bf16_t>(b, gather_stream);
     }
     if (a.tile_ptr && overlap) {
         // join, also after an error above: the caller's stream must not run ahead of work already on the side stream
-        const int rc2 = hip_status(hipStreamWaitEvent(st, a.ev_join, 0), "hipStreamWaitEvent");
+        int rc2 = hip_status(hipEventRecord(a.ev_join, a.side), "hipEventRecord");
+        if (rc2 == GCN_OK) rc2 = hip_status(hipStreamWaitEvent(st, a.ev_join, 0), "hipStreamWaitEvent");
         if (rc == GCN_OK) rc = rc2;
         if (rc == GCN_OK) {
             Epi ep{a.epilogue == kEpiRelu ? kActRelu : kActNone, a.width, a.drop_threshold, a.keep_scale, a.drop_key};

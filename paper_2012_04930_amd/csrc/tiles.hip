@@ -19,7 +19,8 @@
 // (8 + 8 + 8 significant bits: hi = x with the low 16 bits of its encoding cleared, mid likewise from x - hi, lo
 // = the rest, which then has at most 8 significant bits; all three subtractions are exact).  Ones and zeros are
 // exact in bfloat16 too, so three passes of v_mfma_f32_32x32x16_bf16 over the same accumulator add exactly
-// the terms the float32 gather adds, in float32, in another order.  (Values below 2^-110 lose their last bits:
+// the terms the float32 gather adds, in float32, in another order.  The split is done once per aggregation by a
+// pass over the input (k_tile_planes), which also lays the values out in the order the instruction reads them.  (Values below 2^-110 lose their last bits:
 // bfloat16 has float32's exponent range but lo is 2^-16 times smaller.)  bfloat16 input rows need one pass.
 #include <algorithm>
 #include <vector>
@@ -242,19 +243,53 @@ __device__ inline bf16x8 expand_bits(uint32_t w, int sh) {
     return r.v;
 }
 
-// One workgroup (4 waves) per work item = a run of dense tiles of one row block (kTileRows output rows):
-//   dst[rows of the block, col0 .. col0 + 32 NB) = sum over the run's tiles of
-//        bits (kTileRows x 32, zero/one)  x  t[32 ct .. 32 ct + 32, col0 .. col0 + 32 NB).
-// Per tile, the waves load the 32 x 32 NB slab of t together (a thread: 8 consecutive rows of 2 columns), split
-// it into bfloat16 planes and leave them in LDS in the order the matrix instruction wants its second operand:
-// for every column the 8 consecutive-k values of a k-octet in one 16-byte unit.  Then wave (wm, wn) multiplies
-// the bits of its SUB row tiles (32 rows each) with the planes of its JW column blocks: per 16-deep k-step one
-// first operand per row tile, expanded from the bit words in registers, and one 16-byte LDS read per plane and
-// column block.  Two LDS buffers: the slab of the next tile is converted and stored while the current one is
-// multiplied (the conversion's instructions sit between the matrix instructions, which run in their shadow),
-// its loads were issued three tiles earlier; one barrier per tile; no branch inside a step.
-// Rows of t past the matrix (only in the last column tile) read the all-zero row n; their bits are zero.
-// Threads whose columns lie at or past `cols` read column 0 instead; such columns are never stored.
+// ---- step 1: the input in the order the matrix instruction reads its second operand.
+// planes[p][ct][kg][c] is one 16-byte unit: the bfloat16 values of plane p of t[32 ct + 8 kg + 0 .. 7, c], i.e. the
+// eight consecutive-k values of one k-octet of one column (p, ct, kg, c major to minor; c < ld).  Rows at or past n
+// and columns at or past `cols` are zero (ld, the planes' own leading dimension, is cols rounded up to whole blocks
+// of 32).  One thread per (ct, kg, pair of columns): eight rows of two columns in, two units per plane out; the
+// conversion's arithmetic runs here, in a kernel bound by memory, so the product below is left with (almost)
+// nothing but matrix instructions.
+template <typename TIn>
+__global__ __launch_bounds__(kThreads) void k_tile_planes(const TIn *__restrict__ t, int ld_t, int64_t n, int n_ct,
+                                                          int cols, int ld, uint4 *__restrict__ planes) {
+    constexpr int P = Planes<TIn>::kCount;
+    const int pairs = ld / 2;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)n_ct * 4 * pairs) return;
+    const int c2 = (int)(i % pairs);
+    const int kg = (int)((i / pairs) % 4);
+    const int64_t ct = i / ((int64_t)pairs * 4);
+    const int64_t row0 = ct * 32 + kg * 8;
+    uint32_t r[8][2];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        r[k][0] = r[k][1] = 0u;
+        if (row0 + k < n && 2 * c2 < cols) load_pair(t + (row0 + k) * ld_t + 2 * c2, r[k]);   // cols is even
+    }
+    const size_t plane_units = (size_t)n_ct * 4 * ld;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        uint32_t x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x[k] = r[k][c];
+        uint4 o[P];
+        split_column<P>(x, o);
+#pragma unroll
+        for (int p = 0; p < P; ++p) planes[p * plane_units + ((size_t)ct * 4 + kg) * ld + 2 * c2 + c] = o[p];
+    }
+}
+
+// ---- step 2: the product.  One workgroup (4 independent waves, no LDS, no barrier) per work item = a run of dense
+// tiles of one row block (kTileRows output rows) and, with blockIdx.y, a span of 32 NBLK columns:
+//   dst[rows of the block, the span] = sum over the run's tiles of  bits (kTileRows x 32, zero/one) x planes(ct).
+// NBLK = 4: wave w takes column block w (32 columns) of all four row tiles (32 rows each) of the block; NBLK = 2:
+// column block w % 2 of two row tiles; NBLK = 1: one row tile each.  Per tile and 16-deep k-step a wave loads one
+// 16-byte unit per plane and lane straight from memory (lane l: column l % 32 of its block, k-octet l / 32),
+// expands the bit words of its row tiles to bfloat16 ones and zeros in registers, and issues one matrix
+// instruction per row tile and plane, consecutive ones into different accumulators.  Loads run three tiles ahead
+// in three register stages; no branch inside a step.
+// Waves whose column block lies at or past `cols` leave at once.
 struct TileItem {
     int32_t rb;      // row block
     int32_t first;   // index of the run's first dense tile
@@ -262,162 +297,105 @@ struct TileItem {
     int32_t slot;    // -1: the sums go to the output rows; k >= 0: to block k of the partial-sum buffer
 };
 
-template <typename TIn, int NB>
-__global__ __launch_bounds__(kThreads, 3) void k_tiles(const TileItem *__restrict__ items,
-                                                       const int32_t *__restrict__ tile_col,
-                                                       const uint32_t *__restrict__ bits, int64_t n,
-                                                       const TIn *__restrict__ t, int ld_t, float *__restrict__ out,
-                                                       int ld_out, float *__restrict__ partial, int cols) {
-    constexpr int P = Planes<TIn>::kCount;
-    constexpr int JW = NB >= 2 ? 2 : 1;            // column blocks (of 32) per wave
-    constexpr int WN = NB / JW, WM = 4 / WN;       // waves side by side over the columns / stacked over the rows
+template <int P, int NBLK>
+__global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__ items,
+                                                    const int32_t *__restrict__ tile_col,
+                                                    const uint32_t *__restrict__ bits, int64_t n, int n_ct,
+                                                    const uint4 *__restrict__ planes, int ld, float *__restrict__ out,
+                                                    int ld_out, float *__restrict__ partial, int cols) {
+    constexpr int WM = 4 / NBLK;                   // waves stacked over the rows
     constexpr int SUB = kTileRows / 32 / WM;       // row tiles of 32 per wave
-    constexpr int ROW_UNITS = 32 * NB;             // 16-byte units per k-octet of one plane: one per column
-    constexpr int UNITS = 4 * ROW_UNITS;
-    constexpr bool ALL_LOAD = 16 * NB * 4 == kThreads;   // every thread has a piece of the slab
-    static_assert(NB == 1 || NB == 2 || NB == 4, "32, 64 or 128 columns per workgroup");
-    __shared__ uint4 planes[2][P][UNITS];
+    static_assert(NBLK == 1 || NBLK == 2 || NBLK == 4, "32, 64 or 128 columns per workgroup");
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wn = wave % WN, wm = wave / WN;
+    const int wn = wave % NBLK, wm = wave / NBLK;
     // workgroup b runs on XCD b mod 8 and takes place b / 8 of that XCD's sub-list (gridDim.x = 8 x its length)
     const TileItem item = items[(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds];
     if (item.rb < 0) return;                       // an unused place
-    const int col0 = blockIdx.y * 128;             // a second row of workgroups takes columns 128 .. 255
-
-    // loader role: k-octet kg (rows 8 kg .. 8 kg + 7 of the slab), columns 2 c2 and 2 c2 + 1 of the span
-    const int c2 = tid % (16 * NB), kg = tid / (16 * NB);
-    const bool loader = ALL_LOAD || kg < 4;        // whole waves either way
-    const int lcol = col0 + 2 * c2;
-    const TIn *lbase = t + (lcol < cols ? lcol : 0);
-    const int last_row = (int)n;
+    const int col = (blockIdx.y * NBLK + wn) * 32 + l32;
+    if (col - l32 >= cols) return;                 // the whole wave: nothing of its block is inside the matrix
     const int64_t first = item.first;
     const int count = item.count;
+    const size_t plane_units = (size_t)n_ct * 4 * ld;
+    // unit of (plane p, k-step s) for this lane inside tile ct:  p * plane_units + ct * 4 * ld + (2 s + h) * ld + col
+    const uint32_t lane_unit = (uint32_t)(h * ld + col);   // col < ld: the planes hold whole blocks of 32 columns
 
     struct Stage {
-        uint32_t r[8][2];
+        uint4 b[2][P];
         uint32_t w[SUB];
     };
-    // Loads of tile i (clamped into the run, so they are always valid): the slab piece and this wave's bit words;
-    // lane l holds the word of row l % 32 of each of its row tiles.  The tile's column index was fetched by the
+    // Loads of tile i (clamped into the run, so they are always valid).  The tile's column index was fetched by the
     // fill before (ct_next), so no load here waits for another.
     int ct_next = tile_col[first];
     auto fill = [&](int i, Stage &st) {
         const int64_t ti = first + (i < count ? i : count - 1);
         const int ct = ct_next;
         ct_next = tile_col[first + (i + 1 < count ? i + 1 : count - 1)];
-        if (loader) {
-            const int row0 = ct * 32 + kg * 8;
+        const uint4 *base = planes + (size_t)ct * 4 * ld;   // wave-uniform
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                int row = row0 + k;
-                row = row < last_row ? row : last_row;
-                load_pair(lbase + (int64_t)row * ld_t, st.r[k]);
-            }
-        }
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int p = 0; p < P; ++p) st.b[s][p] = base[p * plane_units + (size_t)(2 * s) * ld + lane_unit];
 #pragma unroll
         for (int u = 0; u < SUB; ++u) st.w[u] = bits[ti * kTileRows + (wm * SUB + u) * 32 + l32];
     };
-    auto convert = [&](const Stage &st, int c, uint4 (&o)[P]) {
-        uint32_t x[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) x[k] = st.r[k][c];
-        split_column<P>(x, o);
-    };
-    auto store_units = [&](int buf, int c, const uint4 (&o)[P]) {
-        if (loader) {
-#pragma unroll
-            for (int p = 0; p < P; ++p) planes[buf][p][kg * ROW_UNITS + 2 * c2 + c] = o[p];
-        }
-    };
 
-    f32x16 acc[SUB][JW];
+    f32x16 acc[SUB];
 #pragma unroll
     for (int u = 0; u < SUB; ++u)
 #pragma unroll
-        for (int j = 0; j < JW; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[u][j][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[u][v] = 0.0f;
 
     if (count > 0) {
-        // Three register stages: while tile i is multiplied, the slab of tile i + 1 is converted from registers and
-        // the loads of tiles i + 2 and i + 3 are in flight (a tile's arithmetic is a fraction of a load's latency).
         Stage s0, s1, s2;
-        // free_st holds tile i's bit words (its slab is in LDS already), next_st tile i + 1
-        auto step = [&](int i, Stage &free_st, const Stage &next_st) {
-            uint32_t w_cur[SUB];
-#pragma unroll
-            for (int u = 0; u < SUB; ++u) w_cur[u] = free_st.w[u];
-            fill(i + 3, free_st);
-            const int buf = i & 1;
-            uint4 o0[P], o1[P];
+        auto step = [&](int i, Stage &st) {
             union {
                 uint4 q;
                 bf16x8 v;
-            } b[2][JW][P];
-            // all LDS reads of the step first: the matrix instructions then follow each other without a wait
+            } b[2][P];
+            uint32_t w[SUB];
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int j = 0; j < JW; ++j)
+                for (int p = 0; p < P; ++p) b[s][p].q = st.b[s][p];
 #pragma unroll
-                    for (int p = 0; p < P; ++p)
-                        b[s][j][p].q = planes[buf][p][(2 * s + h) * ROW_UNITS + 32 * (wn * JW + j) + l32];
+            for (int u = 0; u < SUB; ++u) w[u] = st.w[u];
+            fill(i + 3, st);   // the stage is free again: its registers were copied above
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 bf16x8 a[SUB];
 #pragma unroll
-                for (int u = 0; u < SUB; ++u) a[u] = expand_bits(w_cur[u], 16 * s + 8 * h);
-                // plane-major: consecutive matrix instructions go to different accumulators
+                for (int u = 0; u < SUB; ++u) a[u] = expand_bits(w[u], 16 * s + 8 * h);
 #pragma unroll
                 for (int p = 0; p < P; ++p)
 #pragma unroll
                     for (int u = 0; u < SUB; ++u)
-#pragma unroll
-                        for (int j = 0; j < JW; ++j)
-                            acc[u][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[s][j][p].v, acc[u][j], 0, 0, 0);
-                // the next tile's slab, one of this thread's two columns per k-step, in the shadow of the above
-                if (s == 0) convert(next_st, 0, o0);
-                else convert(next_st, 1, o1);
+                        acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[s][p].v, acc[u], 0, 0, 0);
             }
-            store_units(buf ^ 1, 0, o0);
-            store_units(buf ^ 1, 1, o1);
-            __syncthreads();   // tile i + 1 is in LDS; nobody reads the buffer of tile i any more
         };
         fill(0, s0);
         fill(1, s1);
         fill(2, s2);
-        {
-            uint4 o0[P], o1[P];
-            convert(s0, 0, o0);
-            convert(s0, 1, o1);
-            store_units(0, 0, o0);
-            store_units(0, 1, o1);
-        }
-        __syncthreads();
-        for (int i = 0; i < count; i += 3) {   // count is the same for the whole workgroup: the barriers line up
-            step(i, s0, s1);
-            if (i + 1 < count) step(i + 1, s1, s2);
-            if (i + 2 < count) step(i + 2, s2, s0);
+        for (int i = 0; i < count; i += 3) {
+            step(i, s0);
+            if (i + 1 < count) step(i + 1, s1);
+            if (i + 2 < count) step(i + 2, s2);
         }
     }
     // accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4 of the row tile, column l % 32 of the block
-    float *dst = item.slot < 0 ? out : partial + (int64_t)item.slot * kTileRows * ld_out;
-    const int64_t base_row = item.slot < 0 ? (int64_t)item.rb * kTileRows : 0;
+    if (col >= cols) return;
+    // partial sums are kept compact: blocks of kTileRows x cols floats
+    float *dst = item.slot < 0 ? out + (int64_t)item.rb * kTileRows * ld_out
+                               : partial + (int64_t)item.slot * kTileRows * cols;
+    const int ld_dst = item.slot < 0 ? ld_out : cols;
     const int64_t rows_left = n - (int64_t)item.rb * kTileRows;   // rows of this block inside the matrix
 #pragma unroll
-    for (int j = 0; j < JW; ++j) {
-        const int col = col0 + 32 * (wn * JW + j) + l32;
-        if (col < cols) {
+    for (int u = 0; u < SUB; ++u)
 #pragma unroll
-            for (int u = 0; u < SUB; ++u)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = (wm * SUB + u) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                    if (row < rows_left) dst[(base_row + row) * ld_out + col] = acc[u][j][v];
-                }
+        for (int v = 0; v < 16; ++v) {
+            const int row = (wm * SUB + u) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            if (row < rows_left) dst[(int64_t)row * ld_dst + col] = acc[u][v];
         }
-    }
 }
 
 // Row blocks whose tiles were cut into several runs: the runs' partial sums are added to the block's output
@@ -437,9 +415,10 @@ __global__ __launch_bounds__(kThreads) void k_tiles_fold(const TileFold *__restr
     const int64_t r = (int64_t)f.rb * kTileRows + row;
     if (r >= n) return;
     float4 o = *reinterpret_cast<const float4 *>(out + r * ld_out + c0);
+#pragma unroll 8
     for (int k = 0; k < f.slots; ++k) {
         const float4 q =
-            *reinterpret_cast<const float4 *>(partial + ((int64_t)(f.slot0 + k) * kTileRows + row) * ld_out + c0);
+            *reinterpret_cast<const float4 *>(partial + ((int64_t)(f.slot0 + k) * kTileRows + row) * cols + c0);
         o.x += q.x;
         o.y += q.y;
         o.z += q.z;
@@ -452,7 +431,7 @@ __global__ __launch_bounds__(kThreads) void k_tiles_fold(const TileFold *__restr
 
 size_t tiles_capacity(int64_t entries) { return (size_t)(entries / kTileMinEntriesFloor) + 1; }
 size_t tiles_item_capacity(int64_t n_rb, int64_t tile_capacity) {
-    return (size_t)kXcds * (size_t)(2 * n_rb + tile_capacity / kTileRunMin + 16);   // eight padded sub-lists
+    return (size_t)kXcds * (size_t)(2 * n_rb + tile_capacity / kTileChunkMin + 16);   // eight padded sub-lists
 }
 
 int tiles_select(int64_t n, const int64_t *rowptr, const int32_t *col, int min_entries, TileBuffers &tb,
@@ -497,32 +476,37 @@ int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_
     return GCN_OK;
 }
 
-// The work items of the product, from the number of dense tiles of every row block (tile_ptr on the host).  A row
-// block is one item unless it holds far more tiles than the average workgroup would get with every resident
-// workgroup slot busy; then its tiles are cut into runs of about that many, the first run writing the output rows
-// and the others partial sums that k_tiles_fold adds in run order.
-// Order: workgroup b runs on XCD b mod 8 (each XCD has its own L2), so the item list is laid out as eight
-// sub-lists, items[x * per_xcd + i] for workgroup 8 i + x.  The sub-lists are contiguous pieces, holding about
-// equal numbers of tiles, of the sequence: one-item blocks in row order (the blocks of one community read the
-// same input rows and now meet in one L2), then the runs of the cut blocks, runs with the same position in their
-// block next to each other (they read the same input rows too).  Unused places hold rb = -1.
+// The work items of the product, from the number of dense tiles of every row block (tile_ptr on the host).
+// The chip holds kSlots workgroups of k_tiles at a time and hands a freed place to the next workgroup in launch
+// order, so the list is: first one item per ordinary row block (a block with about the average number of tiles per
+// place, or fewer), then the tiles of the blocks that hold far more, cut into short runs that fill whatever places
+// are free until all end together.  The first run of such a block writes the output rows, the others partial sums
+// that k_tiles_fold adds in run order.
+// Layout: workgroup b runs on XCD b mod 8 (each XCD has its own L2), so the list is eight sub-lists,
+// items[x * per_xcd + i] for workgroup 8 i + x.  Each sub-list is a contiguous eighth (by tile count) of the ordinary
+// blocks in row order (the blocks of one community read the same input rows and meet in one L2) followed by a
+// contiguous eighth of the runs, ordered by position inside their block (runs at the same position read the same
+// input rows).  Unused places hold rb = -1.
 int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_t st) {
     const int64_t n_rb = (int64_t)tile_ptr.size() - 1;
     const int64_t total = tile_ptr[n_rb];
-    constexpr int64_t kSlots = 768;   // three workgroups on each of 256 compute units
+    constexpr int64_t kSlots = 512;   // two workgroups on each of 256 compute units (register use of k_tiles)
     int64_t run = (total + kSlots - 1) / kSlots;
     if (run < kTileRunMin) run = kTileRunMin;
-    std::vector<TileItem> seq, cut;
+    int64_t chunk = tunable("tile_chunk", 0);
+    if (chunk <= 0) chunk = run / 3;
+    if (chunk < kTileChunkMin) chunk = kTileChunkMin;
+    std::vector<TileItem> whole, cut;
     std::vector<int> cut_pos;   // position of a run inside its block
     std::vector<TileFold> folds;
     int32_t slots = 0;
     for (int64_t rb = 0; rb < n_rb; ++rb) {
         const int64_t first = tile_ptr[rb], cnt = tile_ptr[rb + 1] - first;
         if (cnt * 2 <= run * 3) {
-            seq.push_back({(int32_t)rb, (int32_t)first, (int32_t)cnt, -1});
+            whole.push_back({(int32_t)rb, (int32_t)first, (int32_t)cnt, -1});
             continue;
         }
-        const int64_t parts = (cnt + run - 1) / run;
+        const int64_t parts = (cnt + chunk - 1) / chunk;
         folds.push_back({(int32_t)rb, slots, (int32_t)(parts - 1), 0});
         for (int64_t k = 0; k < parts; ++k) {
             const int64_t b = first + cnt * k / parts, e = first + cnt * (k + 1) / parts;
@@ -530,16 +514,21 @@ int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_
             cut_pos.push_back((int)k);
         }
     }
-    std::vector<size_t> order(cut.size());
-    for (size_t i = 0; i < order.size(); ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) { return cut_pos[x] < cut_pos[y]; });
-    for (size_t i : order) seq.push_back(cut[i]);
-    // eight contiguous pieces of about equal numbers of tiles (an item counts as at least one)
-    int64_t weight = 0;
-    for (const TileItem &it : seq) weight += it.count > 0 ? it.count : 1;
-    std::vector<size_t> start(kXcds + 1, seq.size());
-    start[0] = 0;
     {
+        std::vector<size_t> order(cut.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+        std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) { return cut_pos[x] < cut_pos[y]; });
+        std::vector<TileItem> sorted;
+        sorted.reserve(cut.size());
+        for (size_t i : order) sorted.push_back(cut[i]);
+        cut.swap(sorted);
+    }
+    // eight contiguous pieces of about equal numbers of tiles (an item counts as at least one)
+    auto eighths = [](const std::vector<TileItem> &seq, std::vector<size_t> &start) {
+        int64_t weight = 0;
+        for (const TileItem &it : seq) weight += it.count > 0 ? it.count : 1;
+        start.assign(kXcds + 1, seq.size());
+        start[0] = 0;
         int64_t done = 0;
         size_t i = 0;
         for (int x = 1; x < kXcds; ++x) {
@@ -550,12 +539,18 @@ int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_
             }
             start[x] = i;
         }
-    }
+    };
+    std::vector<size_t> ws, cs;
+    eighths(whole, ws);
+    eighths(cut, cs);
     size_t per_xcd = 0;
-    for (int x = 0; x < kXcds; ++x) per_xcd = std::max(per_xcd, start[x + 1] - start[x]);
+    for (int x = 0; x < kXcds; ++x) per_xcd = std::max(per_xcd, (ws[x + 1] - ws[x]) + (cs[x + 1] - cs[x]));
     std::vector<TileItem> items(per_xcd * kXcds, TileItem{-1, 0, 0, -1});
-    for (int x = 0; x < kXcds; ++x)
-        for (size_t i = start[x]; i < start[x + 1]; ++i) items[x * per_xcd + (i - start[x])] = seq[i];
+    for (int x = 0; x < kXcds; ++x) {
+        size_t at = x * per_xcd;
+        for (size_t i = ws[x]; i < ws[x + 1]; ++i) items[at++] = whole[i];
+        for (size_t i = cs[x]; i < cs[x + 1]; ++i) items[at++] = cut[i];
+    }
     if (items.size() > tb.item_capacity || folds.size() > (size_t)n_rb || total > 0x7fffffff) {
         set_error("dense tiles: %zu work items exceed the capacity %zu", items.size(), tb.item_capacity);
         return GCN_EINVAL;
@@ -572,23 +567,37 @@ int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_
     return GCN_OK;
 }
 
+size_t tiles_plane_bytes(int64_t n, int cols, int dtype) {
+    const size_t n_ct = (size_t)((n + 31) / 32);
+    return (size_t)(dtype == GCN_BF16 ? 1 : 3) * n_ct * 4 * (size_t)round_up(cols, 32) * 16;
+}
+
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
-    if (a.cols > 256 || a.n_items < 1 || (a.n_slots > 0 && !a.tile_partial)) {
-        set_error("dense tiles: at most 256 columns, and a partial-sum buffer when runs were cut");
+    if (a.cols > 256 || a.n_items < 1 || (a.n_slots > 0 && !a.tile_partial) || !a.tile_planes) {
+        set_error("dense tiles: at most 256 columns, a buffer for the operand planes, and one for partial sums when runs were cut");
         return GCN_EINVAL;
     }
-    const dim3 grid((unsigned)a.n_items, a.cols > 128 ? 2u : 1u);
+    const int n_ct = (int)((a.n + 31) / 32);
+    const int ld = (int)round_up(a.cols, 32);
+    uint4 *planes = static_cast<uint4 *>(a.tile_planes);
+    const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
+    if (a.t_dtype == GCN_BF16)
+        k_tile_planes<bf16_t><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
+            static_cast<const bf16_t *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
+    else
+        k_tile_planes<float><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
+            static_cast<const float *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
+    GCN_LAUNCH_CHECK();
     const TileItem *items = reinterpret_cast<const TileItem *>(a.tile_items);
-#define GCN_TILES(NB)                                                                                                 \
+#define GCN_TILES(NBLK)                                                                                               \
     do {                                                                                                              \
+        const dim3 grid((unsigned)a.n_items, (unsigned)((a.cols + 32 * NBLK - 1) / (32 * NBLK)));                     \
         if (a.t_dtype == GCN_BF16)                                                                                    \
-            k_tiles<bf16_t, NB><<<grid, dim3(kThreads), 0, st>>>(items, a.tile_col, a.bits, a.n,                     \
-                                                                  static_cast<const bf16_t *>(a.t), a.ld_t, dst,     \
-                                                                  ld_dst, a.tile_partial, a.cols);                    \
+            k_tiles<1, NBLK><<<grid, dim3(kThreads), 0, st>>>(items, a.tile_col, a.bits, a.n, n_ct, planes, ld, dst,  \
+                                                              ld_dst, a.tile_partial, a.cols);                        \
         else                                                                                                          \
-            k_tiles<float, NB><<<grid, dim3(kThreads), 0, st>>>(items, a.tile_col, a.bits, a.n,                      \
-                                                                 static_cast<const float *>(a.t), a.ld_t, dst,       \
-                                                                 ld_dst, a.tile_partial, a.cols);                     \
+            k_tiles<3, NBLK><<<grid, dim3(kThreads), 0, st>>>(items, a.tile_col, a.bits, a.n, n_ct, planes, ld, dst,  \
+                                                              ld_dst, a.tile_partial, a.cols);                        \
     } while (0)
     if (a.cols <= 32) GCN_TILES(1);
     else if (a.cols <= 64) GCN_TILES(2);
@@ -596,8 +605,8 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
 #undef GCN_TILES
     GCN_LAUNCH_CHECK();
     if (a.n_folds > 0) {
-        const int64_t threads = (int64_t)a.n_folds * kTileRows * (a.cols / 4);
-        k_tiles_fold<<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
+        const int64_t fthreads = (int64_t)a.n_folds * kTileRows * (a.cols / 4);
+        k_tiles_fold<<<dim3(blocks_for(fthreads, kThreads)), dim3(kThreads), 0, st>>>(
             reinterpret_cast<const TileFold *>(a.tile_folds), a.n_folds, a.n, dst, ld_dst, a.tile_partial, a.cols);
         GCN_LAUNCH_CHECK();
     }
