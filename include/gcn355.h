@@ -22,6 +22,8 @@
  *     *_workspace_bytes calls, 256-byte aligned) and keeps them alive until the matching destroy.
  *     Everything else passed to a create call is copied and may be released once it returns.
  *   - Dense matrices crossing this boundary are row-major, float32, without padding.
+ *   - "Tunable" below means a named knob of gcn_set_tunable, declared with the other measurement aids (kernel
+ *     timing, calibration and ceiling kernels) in gcn355_debug.h; every default is the measured best.
  *   - Return value: GCN_OK (0) or a negative gcn_status.  No call aborts or throws; after a
  *     failure gcn_last_error() returns a thread-local description.  A failed create leaves *out
  *     NULL.  Calls on one model must not overlap in time (one stream at a time).
@@ -89,25 +91,30 @@ int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_trai
 
 /* Dense tiles.  The aggregation of Section 4.1's layer rule (the nnz(A) F term of Section 5.4's cost model)
  * runs in two parts when the adjacency pattern has dense blocks, as the partitions of a community-structured
- * graph do (Section 3): the pattern is cut into aligned 32 x 32 tiles; tiles with at least `tile_min_entries`
- * stored entries (tunable, default 128, allowed 64..1024) are kept as 32 words of 32 bits and multiplied on the
- * matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The split is used when
- * the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this rule, 0 never, 1
- * whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off per call), for
- * matrices of at most 256 columns in either storage type (bfloat16 rows are widened exactly).  Sums are
- * float32 either way; only their order differs.  A non-finite value in a row of the
- * aggregated matrix reaches, through 0 x inf, all 32 rows of the tiles that cover it.
- * Streams: with the split in use the tile product runs on a stream of default priority that the graph owns,
- * beside the gather kernel on the caller's stream; fork and join are done with events, so the caller's stream
- * order is kept, and a third launch adds the two parts.  Tunable "spmm_overlap": 1 = this (default), 0 = one
- * launch after the other on the caller's stream (float32 storage; bfloat16 matrices are then gathered whole).  Because that stream and its events belong to the graph, calls that aggregate over one graph
+ * graph do (Section 3) and as the rows and columns of the vertices that stand in for the other partitions do
+ * (Section 3.1): the pattern is cut into aligned tiles of 128 rows x 32 columns; tiles with at least
+ * `tile_min_entries` stored entries (tunable, default 64, allowed 64..4096) are kept as 128 words of 32 bits and
+ * multiplied on the matrix cores, all other entries stay in a residual CSR that is gathered as usual.  The
+ * split is used when the dense tiles hold at least a quarter of the entries (tunable "spmm_tiles": -1 this rule,
+ * 0 never, 1 whenever there is a dense tile; read at gcn_graph_create, and 0 also switches the form off per
+ * call), for matrices of at most 256 columns in either storage type.
+ * Arithmetic of the tile product: a float32 value is split exactly into three bfloat16 numbers (8 + 8 + 8
+ * significant bits), ones and zeros are exact too, and three passes of the bfloat16 matrix instruction add the
+ * products into float32 accumulators: the same terms as the gather form adds, in float32, in another order
+ * (values below 2^-110 in magnitude lose their last bits).  bfloat16 rows take one pass.  A non-finite value in
+ * a row of the aggregated matrix reaches, through 0 x inf, all 128 rows of the tiles that cover it.
+ * Streams: with the split in use the tile product (a pass that splits and reorders the input, then the product)
+ * runs on a stream of default priority that the graph owns, beside the gather kernel on the caller's stream;
+ * fork and join are done with events, so the caller's stream order is kept, and a last launch adds the two
+ * parts.  Tunable "spmm_overlap": 1 = this (default), 0 = one launch after the other on the caller's stream
+ * (float32 storage; bfloat16 matrices are then gathered whole).  Because that stream and its events belong to the graph, calls that aggregate over one graph
  * (gcn_aggregate, gcn_model_create, gcn_forward, gcn_backward) must not overlap in time, whatever streams they
  * are given.
  * gcn_graph_tile_info: number of dense tiles, stored entries inside them, 1 if the split is in use.
  * gcn_graph_get_tiles (only when in use; any pointer may be NULL; asynchronous on `stream` except *res_nnz):
- *   tile_ptr [dev, ceil(n/32)+1 int64]  dense tiles of row tile i are tile_ptr[i] .. tile_ptr[i+1]
- *   tile_col [dev, n_tiles int32]       their column tiles, ascending inside a row tile
- *   bits     [dev, n_tiles*32 uint32]   word r of tile k: bit c set = entry (32 i + r, 32 tile_col[k] + c)
+ *   tile_ptr [dev, ceil(n/128)+1 int64] dense tiles of row block i (rows 128 i ..) are tile_ptr[i] .. tile_ptr[i+1]
+ *   tile_col [dev, n_tiles int32]       their column tiles (32 columns each), ascending inside a row block
+ *   bits     [dev, n_tiles*128 uint32]  word r of tile k: bit c set = entry (128 i + r, 32 tile_col[k] + c)
  *   res_rowptr [dev, n+1 int64], res_col [dev, *res_nnz int32]  the residual pattern, rows sorted
  *   res_nnz  [host] E minus the entries inside dense tiles */
 int gcn_graph_tile_info(const gcn_graph *g, int64_t *n_tiles, int64_t *nnz_dense, int32_t *in_use);
@@ -255,43 +262,6 @@ int gcn_average_weights(gcn_model *const *models, int32_t n_models, void *stream
 int gcn_adam_update(float *w, const float *dw, float *mom1, float *mom2, size_t count, float lr, float beta1,
                     float beta2, float eps, int64_t step, void *stream);
 
-/* ------------------------------------------------------------------------------------------------
- * Kernel timing for benchmarks: when enabled, every aggregation (SpMM) launch of the calls above is
- * bracketed by HIP events on the launch stream.  gcn_timing_read waits for the events and returns,
- * for launches of the given width since the last reset, their count and total milliseconds.
- */
-int gcn_timing_enable(int on);
-int gcn_timing_reset(void);
-int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms);
-
-/* Benchmark sweeps: sets a named integer knob that selects among equivalent kernel variants or launch
- * shapes.  Results do not depend on any knob beyond rounding order.  Unknown names are stored and ignored.
- *   "cache_ax"          0 / 1 / 2    layer 1 as (A_hat X) W_1 from a cached A_hat X: never / when d_0 <= d_1 (default) /
- *                                    always; read by gcn_model_create
- *   "spmm_tiles"        -1 / 0 / 1   dense tiles: when they hold a quarter of the entries (default) / never / whenever
- *                                    there is one; read by gcn_graph_create, 0 also per call
- *   "tile_min_entries"  64..1024     entries that make a 32 x 32 tile dense (default 128); read by gcn_graph_create
- *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
- *   "spmm_masked"       1 / 0        masked pattern for the last layer's backward aggregation when the train mask
- *                                    holds at most 4/5 of the vertices (default) / never; read by gcn_graph_create
- *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows
- *   "phased_balance"    1 / 0        XCD row ranges of the phased schedule by entries (default) / by rows; read by
- *                                    gcn_graph_create
- *   "phased_group"      0 / 1,2,4,8  column ranges (sixteenths of the ids) per phase of the phased schedule: as many as
- *                                    5 MB of input rows allow (default) / that many
- *   "spmm_u"            4 / 8 / 16   gathers in flight per lane group at 17..32 sixteen-byte pieces per row (default 8) */
-int gcn_set_tunable(const char *name, int64_t value);
-
-/* Measurement aid: launches n_blocks workgroups of 256 threads and writes, for each, the id of the XCD it ran on
- * (out [dev, n_blocks int32]).  The aggregation kernels assume that workgroup b runs on XCD (b + s) mod 8 for
- * a start s that is the same for all workgroups of a launch. */
-int gcn_xcc_ids(int32_t *out, int32_t n_blocks, void *stream);
-
-/* Measurement aid: copies `bytes` (a multiple of 16) from src to dst [dev] with one plain streaming
- * kernel (k_calibration_copy), which reads and writes exactly `bytes` each.  Hardware byte counters
- * collected for the library's kernels are scaled by what they report for this one.  Asynchronous. */
-int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
-
 /* ------------------------------------------------------------------------------------------------------------
  * GraphSAGE with the element-wise mean as propagation rule, two layers, trained in batches (Section 4.1: sample a
  * fixed number of neighbours, aggregate their features, predict; batch size 256, Adam).  Per batch of B target
@@ -343,8 +313,6 @@ enum {
 };
 /* Copies one of the above (of the last batch) to dst [dev, dst_elems elements of its type]. */
 int gcn_sage_get_tensor(gcn_sage *s, int which, void *dst, size_t dst_elems, void *stream);
-/* Pseudo-width under which gcn_timing_read reports the launches of the feature gather (k_sage_concat1). */
-#define GCN_TIMING_SAGE_GATHER (-1)
 
 #ifdef __cplusplus
 }

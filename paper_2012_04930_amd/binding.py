@@ -3,7 +3,8 @@
 Every step of the training path runs in the library's HIP kernels.  PyTorch supplies
 device memory (tensors own the workspaces) and the stream.  There is no CPU fallback:
 if the library has not been built, importing this module's `lib()` raises.
-The Python functions carry the same names as the C entry points in include/gcn355.h.
+The Python functions carry the same names as the C entry points in include/gcn355.h and
+include/gcn355_debug.h.
 """
 from __future__ import annotations
 
@@ -30,6 +31,7 @@ EXPORTS = [
     "gcn_augment_workspace_bytes", "gcn_augment_partition", "gcn_gather_rows", "gcn_average_weights", "gcn_xcc_ids",
     "gcn_sage_workspace_bytes", "gcn_sage_create", "gcn_sage_destroy", "gcn_sage_set_weights", "gcn_sage_forward",
     "gcn_sage_loss_acc", "gcn_sage_backward", "gcn_sage_adam_step", "gcn_sage_get_tensor",
+    "gcn_ceiling_gather", "gcn_ceiling_mfma_bf16",
 ]
 
 _lib = None
@@ -86,7 +88,9 @@ def lib():
         L.gcn_sage_get_tensor.argtypes = [vp, C.c_int, vp, sz, vp]
         L.gcn_timing_enable.argtypes = [C.c_int]
         L.gcn_timing_reset.argtypes = []
-        L.gcn_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double)]
+        L.gcn_timing_read.argtypes = [i32, i32, C.POINTER(i64), C.POINTER(C.c_double)]
+        L.gcn_ceiling_gather.argtypes = [vp, i64, i32, i64, i32, C.c_int, vp, vp]
+        L.gcn_ceiling_mfma_bf16.argtypes = [i64, i32, vp, vp]
         L.gcn_calibration_copy.argtypes = [vp, vp, sz, vp]
         L.gcn_set_tunable.argtypes = [C.c_char_p, i64]
         L.gcn_augment_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
@@ -308,19 +312,40 @@ def gcn_sgd_step(m: Model, lr: float) -> None:
     _check(lib().gcn_sgd_step(m.handle, lr, _stream()))
 
 
-def gcn_timing_enable(on: bool) -> None:
-    _check(lib().gcn_timing_enable(1 if on else 0))
+# parts of gcn_timing_read (gcn_timed_part of include/gcn355_debug.h)
+GCN_TIME_AGGREGATE, GCN_TIME_GATHER, GCN_TIME_TILES, GCN_TIME_PLANES, GCN_TIME_JOIN, GCN_TIME_GEMM_NN, \
+    GCN_TIME_GEMM_TN, GCN_TIME_GEMM_NT, GCN_TIME_LOSS, GCN_TIME_SAGE_GATHER = range(10)
+
+
+def gcn_timing_enable(level) -> None:
+    """0 / False: off; 1 / True: whole aggregations; 2: also their parts, the dense products and the loss."""
+    _check(lib().gcn_timing_enable(int(level)))
 
 
 def gcn_timing_reset() -> None:
     _check(lib().gcn_timing_reset())
 
 
-def gcn_timing_read(width: int):
-    """-> (launches, total milliseconds) of aggregation launches of this width since the last reset."""
+def gcn_timing_read(width: int, part: int = GCN_TIME_AGGREGATE):
+    """-> (launches, total milliseconds) of the timed intervals of (part, width) since the last reset."""
     cnt, ms = C.c_int64(), C.c_double()
-    _check(lib().gcn_timing_read(width, C.byref(cnt), C.byref(ms)))
+    _check(lib().gcn_timing_read(part, width, C.byref(cnt), C.byref(ms)))
     return cnt.value, ms.value
+
+
+def gcn_ceiling_gather(table: torch.Tensor, waves: int, per_wave: int, spread: bool) -> torch.Tensor:
+    """Runs the gather ceiling kernel over table [rows x row_floats float32]; -> the waves' sums."""
+    rows, row_floats = table.shape
+    out = torch.empty((waves, row_floats), dtype=torch.float32, device="cuda")
+    _check(lib().gcn_ceiling_gather(_dev(table, torch.float32), rows, row_floats, waves, per_wave, 1 if spread else 0,
+                                    out.data_ptr(), _stream()))
+    return out
+
+
+def gcn_ceiling_mfma_bf16(waves: int, per_wave: int) -> torch.Tensor:
+    out = torch.empty((waves, 64), dtype=torch.float32, device="cuda")
+    _check(lib().gcn_ceiling_mfma_bf16(waves, per_wave, out.data_ptr(), _stream()))
+    return out
 
 
 def gcn_calibration_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
@@ -389,7 +414,6 @@ def gcn_xcc_ids(n_blocks: int) -> torch.Tensor:
 # ---------------------------------------------------------------------------------------------- GraphSAGE-mean
 GCN_SAGE_W1, GCN_SAGE_W2, GCN_SAGE_DW1, GCN_SAGE_DW2, GCN_SAGE_H1, GCN_SAGE_LOGITS, GCN_SAGE_C1_MEAN, \
     GCN_SAGE_INNER, GCN_SAGE_OUTER = range(9)
-GCN_TIMING_SAGE_GATHER = -1
 
 
 class Sage:

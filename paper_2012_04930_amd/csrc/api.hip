@@ -37,48 +37,48 @@ int64_t tunable(const char *name, int64_t fallback) {
 // ------------------------------------------------------------------------------------------- timing
 namespace {
 struct TimedLaunch {
-    int width;
+    int part, width;
     hipEvent_t start, stop;
+    bool closed;
 };
 std::mutex g_tmutex;
-bool g_timing = false;
+int g_timing = 0;   // 0 off, 1 whole aggregations (and the GraphSAGE gather), 2 also their parts and the dense products
 std::vector<TimedLaunch> g_launches;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_free_events;
-hipEvent_t g_open_stop = nullptr;
 }  // namespace
 
-void timing_begin(int width, hipStream_t st) {
+int timing_open(int part, int width, hipStream_t st) {
     std::lock_guard<std::mutex> lk(g_tmutex);
-    g_open_stop = nullptr;
-    if (!g_timing) return;
+    const int level = (part == kTimeAggregate || part == kTimeSageGather) ? 1 : 2;
+    if (g_timing < level) return -1;
     std::pair<hipEvent_t, hipEvent_t> ev;
     if (!g_free_events.empty()) {
         ev = g_free_events.back();
         g_free_events.pop_back();
     } else {
-        if (hipEventCreate(&ev.first) != hipSuccess) return;
+        if (hipEventCreate(&ev.first) != hipSuccess) return -1;
         if (hipEventCreate(&ev.second) != hipSuccess) {
             (void)hipEventDestroy(ev.first);
-            return;
+            return -1;
         }
     }
     if (hipEventRecord(ev.first, st) != hipSuccess) {
         g_free_events.push_back(ev);
-        return;
+        return -1;
     }
-    g_launches.push_back({width, ev.first, ev.second});
-    g_open_stop = ev.second;
+    g_launches.push_back({part, width, ev.first, ev.second, false});
+    return (int)g_launches.size() - 1;
+}
+
+void timing_close(int handle, hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    if (handle < 0 || handle >= (int)g_launches.size() || g_launches[handle].closed) return;
+    if (hipEventRecord(g_launches[handle].stop, st) == hipSuccess) g_launches[handle].closed = true;
 }
 
 bool timing_enabled() {
     std::lock_guard<std::mutex> lk(g_tmutex);
-    return g_timing;
-}
-
-void timing_end(hipStream_t st) {
-    std::lock_guard<std::mutex> lk(g_tmutex);
-    if (g_open_stop) (void)hipEventRecord(g_open_stop, st);
-    g_open_stop = nullptr;
+    return g_timing != 0;
 }
 
 }  // namespace gcn
@@ -1024,20 +1024,24 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
         }
         if (l == 1 && m->l1_cached) {
             // H_1 = act(P W_1), P = A_hat X
+            const int t_nn = timing_open(kTimeGemmNN, ly.d_out, st);
             int rc = bf ? gemm_bf16_nn(m->pax, g->ldf, ly.wbt, ly.ld_in, ly.h, ly.ld_out, g->n, ly.ld_in, ly.ld_out, nullptr,
                                        &act, st)
                         : gemm_nn((const float *)m->pax, g->ldf, ly.w, ly.ld_out, (float *)ly.h, ly.ld_out, g->n, ly.ld_in,
                                   ly.ld_out, nullptr, &act, st);
+            timing_close(t_nn, st);
             if (rc) return rc;
             h_prev = ly.h;
             ld_prev = ly.ld_out;
             continue;
         }
         // T = D^-1/2 (H_{l-1} W_l)
+        const int t_nn = timing_open(kTimeGemmNN, ly.d_out, st);
         int rc = bf ? gemm_bf16_nn(h_prev, ld_prev, ly.wbt, ly.ld_in, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
                                    g->pb.dinv, nullptr, st)
                     : gemm_nn((const float *)h_prev, ld_prev, ly.w, ly.ld_out, (float *)ly.t, ly.ld_out, g->n, ly.ld_in,
                               ly.ld_out, g->pb.dinv, nullptr, st);
+        timing_close(t_nn, st);
         if (rc) return rc;
         // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
         SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
@@ -1064,8 +1068,10 @@ int gcn_loss_acc(gcn_model *m, float *loss, float *acc, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const gcn_graph *g = m->g;
     Layer &ly = m->layers[m->L - 1];
+    const int t_loss = timing_open(kTimeLoss, ly.d_out, st);
     int rc = loss_forward(g->n, ly.d_out, (const float *)ly.h, ly.ld_out, g->labels, g->mask, g->pb.dinv, g->n_train,
                           ly.dzs, m->dtype, ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st);
+    timing_close(t_loss, st);
     if (rc) return rc;
     m->have_loss = true;
     if (loss || acc) {
@@ -1106,6 +1112,7 @@ int gcn_backward(gcn_model *m, void *stream) {
         if (l == 1 && m->l1_cached) {
             // dW_1 = P^T dZ_1  (dzs of layer 1 was written without D^-1/2)
             int rc;
+            const int t_tn = timing_open(kTimeGemmTN, ly.d_out, st);
             if (bf) {
                 int splits = 0;
                 rc = gemm_bf16_tn_partials(m->pax, g->ldf, ly.dzs, ly.ld_out, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
@@ -1116,6 +1123,7 @@ int gcn_backward(gcn_model *m, void *stream) {
                 rc = gemm_tn((const float *)m->pax, g->ldf, (const float *)ly.dzs, ly.ld_out, ly.dw, ly.ld_out, g->n,
                              ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
             }
+            timing_close(t_tn, st);
             if (rc) return rc;
             continue;
         }
@@ -1127,6 +1135,7 @@ int gcn_backward(gcn_model *m, void *stream) {
         if (rc) return rc;
         // dW_l = H_{l-1}^T G
         const void *h_prev = l > 1 ? m->layers[l - 2].h : g->x;
+        const int t_tn = timing_open(kTimeGemmTN, ly.d_out, st);
         if (bf) {
             int splits = 0;
             rc = gemm_bf16_tn_partials(h_prev, ly.ld_in, ly.g, ly.ld_out, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
@@ -1137,15 +1146,18 @@ int gcn_backward(gcn_model *m, void *stream) {
             rc = gemm_tn((const float *)h_prev, ly.ld_in, (const float *)ly.g, ly.ld_out, ly.dw, ly.ld_out, g->n,
                          ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
         }
+        timing_close(t_tn, st);
         if (rc) return rc;
         if (l > 1) {
             // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
             Layer &lp = m->layers[l - 2];
             const float *next_scale = (l == 2 && m->l1_cached) ? nullptr : g->pb.dinv;   // no aggregation follows
+            const int t_nt = timing_open(kTimeGemmNT, lp.d_out, st);
             rc = bf ? gemm_bf16_nt(ly.g, ly.ld_out, ly.wb, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out,
                                    next_scale, lp.h, lp.ld_out, keep_scale, st)
                     : gemm_nt((const float *)ly.g, ly.ld_out, ly.w, ly.ld_out, (float *)lp.dzs, lp.ld_out, g->n,
                               ly.ld_out, lp.ld_out, next_scale, (const float *)lp.h, lp.ld_out, keep_scale, st);
+            timing_close(t_nt, st);
             if (rc) return rc;
         }
     }
@@ -1277,25 +1289,23 @@ int gcn_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)
     return calibration_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
-int gcn_timing_enable(int on) {
+int gcn_timing_enable(int level) {
     std::lock_guard<std::mutex> lk(g_tmutex);
-    g_timing = on != 0;
+    g_timing = level < 0 ? 0 : (level > 2 ? 2 : level);
     return GCN_OK;
 }
-
 int gcn_timing_reset(void) {
     std::lock_guard<std::mutex> lk(g_tmutex);
     for (auto &t : g_launches) g_free_events.push_back({t.start, t.stop});
     g_launches.clear();
     return GCN_OK;
 }
-
-int gcn_timing_read(int32_t width, int64_t *launches, double *total_ms) {
+int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *total_ms) {
     std::lock_guard<std::mutex> lk(g_tmutex);
     int64_t cnt = 0;
     double ms = 0.0;
     for (auto &t : g_launches) {
-        if (t.width != width) continue;
+        if (t.part != part || t.width != width || !t.closed) continue;
         GCN_HIP(hipEventSynchronize(t.stop));
         float one = 0.f;
         GCN_HIP(hipEventElapsedTime(&one, t.start, t.stop));

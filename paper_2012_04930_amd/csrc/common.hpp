@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/gcn355.h"
+#include "../../include/gcn355_debug.h"
 #include "epilogue.hpp"
 
 namespace gcn {
@@ -303,9 +304,17 @@ int gemm_bf16_tn_partials(const void *a, int lda, const void *b, int ldb, int ld
                           float *partials, size_t partial_floats, int *splits_out, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
-// Event timing of aggregation launches (api.hip)
-void timing_begin(int width, hipStream_t st);
-void timing_end(hipStream_t st);
+// Event timing of launches (api.hip): timing_open records an event on the stream the work is about to be launched
+// on and returns a handle (-1 when the part is not being timed); timing_close records the closing event.
+// `part` is a gcn_timed_part of include/gcn355_debug.h.
+int timing_open(int part, int width, hipStream_t st);
+void timing_close(int handle, hipStream_t st);
 bool timing_enabled();
+enum {
+    kTimeAggregate = GCN_TIME_AGGREGATE, kTimeGather = GCN_TIME_GATHER, kTimeTiles = GCN_TIME_TILES,
+    kTimePlanes = GCN_TIME_PLANES, kTimeJoin = GCN_TIME_JOIN, kTimeGemmNN = GCN_TIME_GEMM_NN,
+    kTimeGemmTN = GCN_TIME_GEMM_TN, kTimeGemmNT = GCN_TIME_GEMM_NT, kTimeLoss = GCN_TIME_LOSS,
+    kTimeSageGather = GCN_TIME_SAGE_GATHER
+};
 
 }  // namespace gcn

@@ -399,10 +399,10 @@ int gcn_sage_forward(gcn_sage *s, const int32_t *batch, int32_t n_batch, uint64_
     k_sage_sample<<<dim3(blocks_for(n1 * S1, kThreads)), dim3(kThreads), 0, st>>>(
         g->pb.rowptr, g->pb.col, s->nodes1, n1, S1, level_key(s->seed, step, 1), s->outer);
     GCN_LAUNCH_CHECK();
-    timing_begin(GCN_TIMING_SAGE_GATHER, st);
+    const int t_gather = timing_open(kTimeSageGather, 0, st);
     k_sage_concat1<<<dim3(blocks_for(n1 * (s->ldf / 4), kThreads)), dim3(kThreads), 0, st>>>(
         static_cast<const float *>(g->x), s->ldf, s->nodes1, s->outer, S1, n1, s->c1);
-    timing_end(st);
+    timing_close(t_gather, st);
     GCN_LAUNCH_CHECK();
     // a few thousand rows against 1216 of shared dimension: split that dimension so that the chip fills
     rc = gemm_nn_splitk(s->c1, 2 * s->ldf, s->w1, s->ldh, s->h1, s->ldh, n1, 2 * s->ldf, s->ldh, true, s->partials,

@@ -573,7 +573,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
                   (long long)a.n_heavy, (long long)a.n, a.t_dtype, a.out_dtype);
         return GCN_EINVAL;
     }
-    timing_begin(a.width, st);
+    const int t_all = timing_open(kTimeAggregate, a.width, st);
     SpmmArgs b = a;
     b.finish_mode = kFinishRow;
     int rc = GCN_OK;
@@ -582,7 +582,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
                          (a.out_dtype == GCN_F32 || a.gather_sums) && tunable("spmm_overlap", 1) != 0;
     if (a.tile_ptr && !overlap && a.out_dtype != GCN_F32) {
         set_error("aggregation: dense tiles with a bfloat16 output need the side stream and both sum buffers");
-        timing_end(st);
+        timing_close(t_all, st);
         return GCN_EINVAL;
     }
     // Side by side: the tile product on the side stream, the gather over the residual entries on the caller's (knob
@@ -609,9 +609,11 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         b.finish_mode = kFinishAddStored;
     }
     if (rc == GCN_OK) {
+        const int t_gather = timing_open(kTimeGather, a.width, gather_stream);
         if (b.t_dtype == GCN_F32) rc = launch_by_width<float, float>(b, gather_stream);
         else if (b.out_dtype == GCN_F32) rc = launch_by_width<bf16_t, float>(b, gather_stream);
         else rc = launch_by_width<bf16_t, bf16_t>(b, gather_stream);
+        timing_close(t_gather, gather_stream);
     }
     if (a.tile_ptr && overlap) {
         // join, also after an error above: the caller's stream must not run ahead of work already on the side stream
@@ -619,6 +621,7 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         if (rc2 == GCN_OK) rc2 = hip_status(hipStreamWaitEvent(st, a.ev_join, 0), "hipStreamWaitEvent");
         if (rc == GCN_OK) rc = rc2;
         if (rc == GCN_OK) {
+            const int t_join = timing_open(kTimeJoin, a.width, st);
             Epi ep{a.epilogue == kEpiRelu ? kActRelu : kActNone, a.width, a.drop_threshold, a.keep_scale, a.drop_key};
             const int64_t quads = a.n * (a.cols / 4);
             const dim3 grid((unsigned)((quads + kThreads - 1) / kThreads));
@@ -631,9 +634,10 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
                                                                      a.gather_sums, a.cols, a.tile_sums, a.cols,
                                                                      a.dinv, a.n, a.cols, ep);
             rc = hip_status(hipGetLastError(), "k_join_parts launch");
+            timing_close(t_join, st);
         }
     }
-    timing_end(st);
+    timing_close(t_all, st);
     return rc;
 }
 

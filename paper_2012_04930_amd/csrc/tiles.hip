@@ -494,7 +494,7 @@ int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_
     int64_t run = (total + kSlots - 1) / kSlots;
     if (run < kTileRunMin) run = kTileRunMin;
     int64_t chunk = tunable("tile_chunk", 0);
-    if (chunk <= 0) chunk = run / 3;
+    if (chunk <= 0) chunk = run / 2;
     if (chunk < kTileChunkMin) chunk = kTileChunkMin;
     std::vector<TileItem> whole, cut;
     std::vector<int> cut_pos;   // position of a run inside its block
@@ -581,6 +581,7 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     const int ld = (int)round_up(a.cols, 32);
     uint4 *planes = static_cast<uint4 *>(a.tile_planes);
     const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
+    const int t_planes = timing_open(kTimePlanes, a.width, st);
     if (a.t_dtype == GCN_BF16)
         k_tile_planes<bf16_t><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
             static_cast<const bf16_t *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
@@ -588,6 +589,8 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
         k_tile_planes<float><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
             static_cast<const float *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
     GCN_LAUNCH_CHECK();
+    timing_close(t_planes, st);
+    const int t_tiles = timing_open(kTimeTiles, a.width, st);
     const TileItem *items = reinterpret_cast<const TileItem *>(a.tile_items);
 #define GCN_TILES(NBLK)                                                                                               \
     do {                                                                                                              \
@@ -610,6 +613,7 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
             reinterpret_cast<const TileFold *>(a.tile_folds), a.n_folds, a.n, dst, ld_dst, a.tile_partial, a.cols);
         GCN_LAUNCH_CHECK();
     }
+    timing_close(t_tiles, st);
     return GCN_OK;
 }
 
