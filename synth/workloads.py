@@ -148,6 +148,22 @@ def rmat_large(seed: int = 0, scale: float = 1.0) -> Workload:
                     epochs=5, dtype="bf16")
 
 
+def planted_classes(seed: int = 0, n: int = 20_000, n_comm: int = 40, avg_degree: float = 30.0, p_intra: float = 0.7,
+                    f: int = 64, hidden: int = 32, signal: float = 0.35, train_frac: float = 0.7) -> Workload:
+    """A community graph whose labels can be learnt, for the training scheme of Section 3.2 (partitions, one model
+    copy per worker, parameter averaging): n vertices in n_comm equal communities (blocks of consecutive ids),
+    power-law degrees, a share p_intra of the edges inside the communities; label = community; features = signal
+    times a seeded unit-variance centroid of the class plus N(0, 1) noise, so one vertex alone says little and the
+    neighbourhood mean says a lot.  mask: train_frac of the vertices; extra["heldout"]: all the others."""
+    rowptr, col, comm = graphs.community_power_law(n, n_comm, avg_degree, 2.5, seed, p_intra=p_intra)
+    dims = [f, hidden, n_comm]
+    centroids = rng.normal_f32(seed, 7400, n_comm * f).reshape(n_comm, f)
+    x = (signal * centroids[comm] + _features(seed, n, f)).astype(np.float32)
+    mask = _bernoulli_mask(seed, n, train_frac)
+    return Workload("planted_%d_classes" % n_comm, n, n, rowptr, col, x, comm.astype(np.int32), mask, dims,
+                    glorot_weights(dims, seed), epochs=30, extra={"heldout": (1 - mask).astype(np.uint8)})
+
+
 BY_NAME = {
     "c1": tiny,
     "c2": chung_lu_mid,

@@ -176,3 +176,42 @@ def test_workers_train_then_average_parameters(B, oracle):
     # training continues from the aggregate
     B.gcn_forward(models[0], True)
     assert np.isfinite(B.gcn_loss_acc(models[0])[0])
+
+
+def test_training_scheme_on_streams_follows_the_oracle_for_several_epochs(B, oracle):
+    """Section 3.2 as a whole: three workers on three streams, every epoch one full-batch step each on its own
+    extended partition (Algorithm 1, overlap 20 %), then the parameter average.  The oracle runs the same scheme on
+    the CPU; the averaged weights are compared after every epoch, and so are the workers' losses."""
+    from paper_2012_04930_amd import partition_training as PT
+    wl = workloads.planted_classes(n=1800, n_comm=6, avg_degree=12.0, f=24, hidden=16)
+    n_parts, overlap, seed, epochs = 3, 0.2, 7, 4
+    part = (np.arange(wl.n) // (wl.n // n_parts)).clip(max=n_parts - 1).astype(np.int32)
+    d = H.to_dev(wl)
+    workers = PT.Workers(d["rowptr"], d["col"], d["x"], d["labels"], d["mask"], torch.from_numpy(part).cuda(), n_parts,
+                         overlap, wl.dims, wl.weights, seed=seed, sampled_vertices_train=True)
+    # the oracle's workers
+    subs = []
+    for p in range(n_parts):
+        ov, onl, _ = SA.augmented_partition(wl.n, wl.rowptr, wl.col, part, n_parts, p, overlap, seed)
+        orp, ocl = SA.induced_subgraph(wl.n, wl.rowptr, wl.col, ov)
+        subs.append((oracle.canonicalise(len(ov), orp, ocl), wl.x[ov], wl.labels[ov], wl.mask[ov]))
+        assert workers.sizes[p][0] == len(ov) and workers.sizes[p][1] == onl
+    ws = [w.astype(np.float64) for w in wl.weights]
+    lr = 0.5
+    for e in range(epochs):
+        stats = workers.epoch(lr, "sgd")
+        new, ref_loss = [], []
+        for og, x, y, msk in subs:
+            w_p, tr = oracle.train_epoch(og, x, ws, y, msk, lr)
+            new.append(w_p)
+            ref_loss.append(tr.loss)
+        ws = [np.mean([w_p[l] for w_p in new], axis=0) for l in range(len(ws))]
+        np.testing.assert_allclose([s[0] for s in stats], ref_loss, rtol=2e-4)
+        for l, got in enumerate(workers.weights()):
+            H.assert_close(got.cpu().numpy(), ws[l], rtol=2e-4, what="averaged W%d after epoch %d" % (l + 1, e + 1))
+    # it learns: the averaged model classifies the held-out vertices of the whole graph far better than chance (1/6)
+    ev = PT.Evaluator(d["rowptr"], d["col"], d["x"], d["labels"],
+                      torch.from_numpy(wl.extra["heldout"]).cuda(), wl.dims)
+    for _ in range(40):
+        workers.epoch(lr, "sgd", read_back=False)
+    assert ev(workers.weights())[1] > 0.5
