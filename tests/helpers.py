@@ -31,6 +31,7 @@ def assert_close(gpu, ref, rtol=RTOL_F32, what=""):
     worst = int(np.argmax(err - bound)) if err.size else 0
     assert np.all(err <= bound), "%s: |diff| %.3e > bound %.3e at flat index %d (ref %.6e, rms %.3e)" % (
         what, err.flat[worst], bound.flat[worst], worst, ref.flat[worst], rms)
+    return float(np.max(err / np.maximum(bound, np.finfo(np.float64).tiny))) if err.size else 0.0
 
 
 def to_dev(wl):
@@ -166,19 +167,23 @@ def oracle_epoch(O, wl, lr=None, dropout_p=0.0, seed=0, training=True, gpu=None,
     return og, tr, new
 
 
-def compare_epoch(O, wl, gpu, tr, new_w, rtol=RTOL_F32):
+def compare_epoch(O, wl, gpu, tr, new_w, rtol=RTOL_F32, say=None, rtol_mid=None):
     """Logits, loss, weight gradients and updated weights are held to rtol (the stated bar).  In bfloat16
     mode the backward intermediates dZ_l and G_l have each passed through up to three bfloat16 roundings
-    (unit roundoff 2^-9 each) and a short dot product with cancellation, so they are held to 2 * rtol.
+    (unit roundoff 2^-9 each) and a short dot product with cancellation, so they are held to 1.5 * rtol (measured
+    at full size: the 2.4 M-vertex three-layer workload reaches 1.10 x rtol on dZ_1 and 1.02 x rtol on dZ_2, the
+    benchmark partition 0.46 x rtol; every other tensor of every workload stays below rtol).
 
     Everything that does not pass a hidden layer's ReLU decision (activations, logits, loss, accuracy and the last
     layer's dZ, G, dW, W) is compared with the oracle's own run.  The tensors below it are compared with the same
     run when no decision differs, else with trace.adjusted (see oracle_epoch)."""
     nl = len(wl.dims) - 1
-    rtol_mid = rtol if rtol <= RTOL_F32 else 2 * rtol
+    if rtol_mid is None:
+        rtol_mid = rtol if rtol <= RTOL_F32 else 1.5 * rtol
+    used = {}       # tensor -> worst observed |diff| / bound (1 = at the bound)
     for l in range(1, nl):
-        assert_close(gpu["H"][l - 1], tr.H[l], rtol, "H%d" % l)
-    assert_close(gpu["logits"], tr.Z[-1], rtol, "logits")
+        used["H%d" % l] = assert_close(gpu["H"][l - 1], tr.H[l], rtol, "H%d" % l)
+    used["logits"] = assert_close(gpu["logits"], tr.Z[-1], rtol, "logits")
     assert abs(gpu["loss"] - tr.loss) <= rtol * abs(tr.loss), ("loss", gpu["loss"], tr.loss)
     # accuracy is an integer decided by floating point: both sides decide on the same fp32 logits
     _, correct_on_gpu_logits, n_train, _ = O.loss_acc(gpu["logits"].astype(np.float64), wl.labels, wl.mask,
@@ -194,11 +199,17 @@ def compare_epoch(O, wl, gpu, tr, new_w, rtol=RTOL_F32):
     below_w = getattr(tr, "adjusted_w", None) or new_w
     for l in range(nl, 0, -1):
         ref, ref_w = (tr, new_w) if l == nl else (below, below_w)
-        assert_close(gpu["dZ"][l - 1], ref.dZ[l - 1], rtol_mid, "dZ%d" % l)
+        used["dZ%d" % l] = assert_close(gpu["dZ"][l - 1], ref.dZ[l - 1], rtol_mid, "dZ%d" % l)
         if gpu["G"][l - 1] is not None:
-            assert_close(gpu["G"][l - 1], ref.G[l - 1], rtol_mid, "G%d" % l)
-        assert_close(gpu["dW"][l - 1], ref.dW[l - 1], rtol, "dW%d" % l)
-        assert_close(gpu["W"][l - 1], ref_w[l - 1], rtol, "W%d after SGD" % l)
+            used["G%d" % l] = assert_close(gpu["G"][l - 1], ref.G[l - 1], rtol_mid, "G%d" % l)
+        used["dW%d" % l] = assert_close(gpu["dW"][l - 1], ref.dW[l - 1], rtol, "dW%d" % l)
+        used["W%d" % l] = assert_close(gpu["W"][l - 1], ref_w[l - 1], rtol, "W%d after SGD" % l)
+    line = "worst |diff| / bound (rtol %g, dZ and G %g): " % (rtol, rtol_mid) + \
+        ", ".join("%s %.2f" % (k, v) for k, v in used.items())
+    print(line)
+    if say:
+        say(line)
+    return used
 
 
 TILE_ROWS = 128     # a dense tile covers 128 rows by 32 columns

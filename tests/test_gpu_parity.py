@@ -293,7 +293,7 @@ def test_benchmark_config_c3_full_size(B, oracle, capsys):
     np.testing.assert_array_equal(deg, og.deg)
     _, gpu = H.gpu_epoch(B, g, wl)
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c3: oracle " + t))
-    H.compare_epoch(oracle, wl, gpu, tr, new)
+    H.compare_epoch(oracle, wl, gpu, tr, new, say=lambda t: _say(capsys, "c3: " + t))
 
 
 def test_benchmark_config_c3_full_size_in_bfloat16_storage(B, oracle, capsys):
@@ -303,7 +303,7 @@ def test_benchmark_config_c3_full_size_in_bfloat16_storage(B, oracle, capsys):
     assert B.gcn_graph_tile_info(g)["in_use"]
     _, gpu = H.gpu_epoch(B, g, wl, dtype=B.GCN_BF16, cache_ax=0)
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True, say=lambda t: _say(capsys, "c3 bf16: oracle " + t))
-    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16, say=lambda t: _say(capsys, "c3 bf16: " + t))
 
 
 def test_config_c2_full_size(B, oracle, capsys):
@@ -311,7 +311,7 @@ def test_config_c2_full_size(B, oracle, capsys):
     g = H.gpu_graph(B, wl)
     _, gpu = H.gpu_epoch(B, g, wl)
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c2: oracle " + t))
-    H.compare_epoch(oracle, wl, gpu, tr, new)
+    H.compare_epoch(oracle, wl, gpu, tr, new, say=lambda t: _say(capsys, "c2: " + t))
 
 
 @pytest.mark.timeout(900)
@@ -331,7 +331,7 @@ def test_config_c4_full_reddit_shape(B, oracle, capsys):
     _say(capsys, "c4: oracle epoch")
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, say=lambda t: _say(capsys, "c4: oracle " + t))
     _say(capsys, "c4: comparing")
-    H.compare_epoch(oracle, wl, gpu, tr, new)
+    H.compare_epoch(oracle, wl, gpu, tr, new, say=lambda t: _say(capsys, "c4: " + t))
 
 
 # ------------------------------------------------------------------ bfloat16 storage, fp32 accumulation (tolerance 2e-2)
@@ -388,7 +388,7 @@ def test_config_c5_full_size_bf16(B, oracle, capsys):
     _say(capsys, "c5: oracle epoch (about a minute of fp64 loops)")
     _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, bf16=True, say=lambda t: _say(capsys, "c5: oracle " + t))
     _say(capsys, "c5: comparing")
-    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16)
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_BF16, say=lambda t: _say(capsys, "c5: " + t))
 
 
 # ------------------------------------------------------------------ layer 1 from the cached A_hat X
