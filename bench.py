@@ -286,7 +286,9 @@ def main() -> int:
                     kernels["%s.w%d" % (name, w)] = {"launches_per_epoch": round(cnt / k_steps, 2),
                                                      "avg_ms": round(ms / cnt, 5),
                                                      "ms_per_epoch": round(ms / k_steps, 5)}
-        ceil = ceilings(B, torch, n + 1, (wl.dims[1] + 15) // 16 * 16)
+        # the gather ceilings are taken on a table of the widest aggregated matrix's size and row length in bytes
+        w_top = max(d for d in wl.dims[1:])
+        ceil = ceilings(B, torch, n + 1, (w_top + 15) // 16 * 16 * esize // 4)
         # the dominant kernel: the one with the most time per epoch among the parts (not the wholes)
         parts = {k: v for k, v in kernels.items() if not k.startswith("aggregation.")}
         if parts:
@@ -300,15 +302,19 @@ def main() -> int:
                 # pattern: `avg` averages both, so do the bytes
                 by = gather_bytes(E_res, n, ld, esize)
                 achieved = by / avg / 1e6
-                peak = ceil["gather_l2_hits_GBps"]
+                # a gathered matrix that fits the last-level cache (256 MB) is served by the caches: the ceiling is the
+                # measured all-L2-hit gather rate; a larger one is served by HBM: the ceiling is the HBM peak
+                cached = (n + 1) * ld * esize <= (256 << 20)
+                peak = ceil["gather_l2_hits_GBps"] if cached else HBM_PEAK_GBS
                 traffic = read_traffic(wl.name, "gather", w) if args.dtype is None else None
-                roofline = {"bound": "cache", "kernel": "k_spmm_phased | k_spmm_wave + k_spmm_group: gather over the "
+                roofline = {"bound": "cache" if cached else "hbm", "kernel": "k_spmm_phased | k_spmm_wave + k_spmm_group: gather over the "
                             + ("%d entries outside the dense tiles" % E_res if tile_info["in_use"] else "whole pattern")
                             + ", width %d" % w,
                             "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s",
                             "frac": round(achieved / peak, 4),
-                            "peak_is": "gather ceiling measured in this run: every gather an L2 hit, table of the "
-                                       "aggregated matrix's size (gcn_ceiling_gather)",
+                            "peak_is": ("gather ceiling measured in this run: every gather an L2 hit, table of the "
+                                        "aggregated matrix's size (gcn_ceiling_gather)") if cached else
+                                       "HBM peak: the gathered matrix is larger than the last-level cache",
                             "bytes_per_launch": by, "avg_launch_ms": avg,
                             "traffic": (traffic["fetch_bytes"] + traffic["write_bytes"]) if traffic else None,
                             "traffic_detail": traffic,
