@@ -280,13 +280,13 @@ __global__ __launch_bounds__(kThreads) void k_tile_planes(const TIn *__restrict_
     }
 }
 
-// ---- step 2: the product.  One workgroup (4 independent waves, no LDS, no barrier) per work item = a run of dense
+// ---- step 2: the product.  One workgroup (4 independent waves; LDS holds only a 128-byte table) per work item = a run of dense
 // tiles of one row block (kTileRows output rows) and, with blockIdx.y, a span of 32 NBLK columns:
 //   dst[rows of the block, the span] = sum over the run's tiles of  bits (kTileRows x 32, zero/one) x planes(ct).
 // NBLK = 4: wave w takes column block w (32 columns) of all four row tiles (32 rows each) of the block; NBLK = 2:
 // column block w % 2 of two row tiles; NBLK = 1: one row tile each.  Per tile and 16-deep k-step a wave loads one
 // 16-byte unit per plane and lane straight from memory (lane l: column l % 32 of its block, k-octet l / 32),
-// expands the bit words of its row tiles to bfloat16 ones and zeros in registers, and issues one matrix
+// turns the bit words of its row tiles into bfloat16 ones and zeros through a 16-entry table, and issues one matrix
 // instruction per row tile and plane, consecutive ones into different accumulators.  Loads run three tiles ahead
 // in three register stages; no branch inside a step.
 // Waves whose column block lies at or past `cols` leave at once.
@@ -309,6 +309,14 @@ __global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % NBLK, wm = wave / NBLK;
+    // entry e of the table: bit i of e -> bfloat16 one (0x3F80) or zero in element i, i = 0..3
+    __shared__ uint2 lut[16];
+    if (tid < 16) {
+        const uint32_t e = (uint32_t)tid;
+        lut[tid] = make_uint2(((e & 1u) ? 0x3F80u : 0u) | ((e & 2u) ? 0x3F800000u : 0u),
+                              ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u));
+    }
+    __syncthreads();   // the only barrier: before any wave leaves
     // workgroup b runs on XCD b mod 8 and takes place b / 8 of that XCD's sub-list (gridDim.x = 8 x its length)
     const TileItem item = items[(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds];
     if (item.rb < 0) return;                       // an unused place
@@ -348,30 +356,38 @@ __global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__
 
     if (count > 0) {
         Stage s0, s1, s2;
-        auto step = [&](int i, Stage &st) {
+        // Bits to operands: four bits pick one of the 16 entries of a table in LDS, each four bfloat16 ones and
+        // zeros (8 bytes; the 16 entries lie in 32 different banks and lanes that read the same entry share it, so
+        // the reads never conflict).  Two table reads per row tile and k-step instead of ten vector instructions,
+        // which on this chip do not run in the shadow of the matrix instructions.
+        auto operand = [&](uint32_t w, int sh) {
             union {
-                uint4 q;
+                uint2 half[2];
                 bf16x8 v;
-            } b[2][P];
-            uint32_t w[SUB];
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int p = 0; p < P; ++p) b[s][p].q = st.b[s][p];
-#pragma unroll
-            for (int u = 0; u < SUB; ++u) w[u] = st.w[u];
-            fill(i + 3, st);   // the stage is free again: its registers were copied above
+            } r;
+            r.half[0] = lut[(w >> sh) & 15u];
+            r.half[1] = lut[(w >> (sh + 4)) & 15u];
+            return r.v;
+        };
+        auto step = [&](int i, Stage &st) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 bf16x8 a[SUB];
 #pragma unroll
-                for (int u = 0; u < SUB; ++u) a[u] = expand_bits(w[u], 16 * s + 8 * h);
+                for (int u = 0; u < SUB; ++u) a[u] = operand(st.w[u], 16 * s + 8 * h);
 #pragma unroll
-                for (int p = 0; p < P; ++p)
+                for (int p = 0; p < P; ++p) {
+                    union {
+                        uint4 q;
+                        bf16x8 v;
+                    } b;
+                    b.q = st.b[s][p];
 #pragma unroll
                     for (int u = 0; u < SUB; ++u)
-                        acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[s][p].v, acc[u], 0, 0, 0);
+                        acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b.v, acc[u], 0, 0, 0);
+                }
             }
+            fill(i + 3, st);   // the stage's registers have been read: its next tile's loads go out now
         };
         fill(0, s0);
         fill(1, s1);
