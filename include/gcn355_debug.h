@@ -49,6 +49,12 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  * shapes.  Results do not depend on any knob beyond rounding order.  Unknown names are stored and ignored.
  *   "cache_ax"          0 / 1 / 2    layer 1 as (A_hat X) W_1 from a cached A_hat X: never / when d_0 <= d_1 (default) /
  *                                    always; read by gcn_model_create
+ *   "gemm_split"        1 / 0        float32 models: layer 1's feature transform on the bfloat16 matrix instruction
+ *                                    from three-plane operands (default) / on the float32 instruction; read by
+ *                                    gcn_model_workspace_bytes and gcn_model_create
+ *   "tile_slots"        >= 256       workgroups of the tile product the chip is taken to hold at a time when its
+ *                                    work items are planned (default 768); read by gcn_graph_create
+ *   "tile_run_min"      >= 8         a row block with up to 1.5 x this many tiles is never cut (default 16)
  *   "spmm_tiles"        -1 / 0 / 1   dense tiles: when they hold a quarter of the entries (default) / never / whenever
  *                                    there is one; read by gcn_graph_create, 0 also per call
  *   "tile_min_entries"  64..4096     entries that make a 128 x 32 tile dense (default 64); read by gcn_graph_create
@@ -57,6 +63,8 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
  *   "spmm_tiles_first"  0 / 1        which of the two goes to the graph's own stream: the tile product (default) /
  *                                    the gather
+ *   "fused_planes"      1 / 0        float32 models: the dense product that writes an aggregation's input also writes the
+ *                                    tile product's operand planes (default) / a separate pass does
  *   "spmm_masked"       1 / 0        masked pattern for the last layer's backward aggregation when the train mask
  *                                    holds at most 4/5 of the vertices (default) / never; read by gcn_graph_create
  *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows

@@ -124,6 +124,11 @@ struct gcn_model {
     bool l1_cached = false;
     void *pax = nullptr;  // (n + 1) x ldf, storage type
     void *xs = nullptr;   // (n + 1) x ldf: D^-1/2 X, only used while P is built
+    // Layer 1's feature transform on the bfloat16 matrix instruction (float32 models): the constant left operand
+    // (X, or P) is packed once, W_1^T before each product.
+    bool l1_split = false;
+    void *sp_a = nullptr;    // packed left operand [n x ld_in]
+    void *sp_wt = nullptr;   // packed right operand [ld_out x ld_in]
 };
 
 namespace {
@@ -324,6 +329,11 @@ void carve_model(Carver &c, gcn_model &m) {
         m.pax = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
         m.xs = c.take<char>((size_t)(n + 1) * m.g->ldf * es);
     }
+    if (m.l1_split) {
+        const Layer &l1 = m.layers[0];
+        m.sp_a = c.take<char>(packed_bytes(n, l1.ld_in, true));
+        m.sp_wt = c.take<char>(packed_bytes(l1.ld_out, l1.ld_in, false));
+    }
     int widest = 0;   // columns of the widest single aggregation launch
     for (auto &ly : m.layers) widest = ly.ld_out > widest ? ly.ld_out : widest;
     if (m.l1_cached) {   // P = A_hat X is built in slabs of 256 (float32) or 512 (bfloat16) columns
@@ -349,6 +359,10 @@ bool want_l1_cached(int32_t n_layers, const int32_t *dims) {
     if (n_layers < 2 || knob <= 0) return false;
     return knob >= 2 || dims[0] <= dims[1];
 }
+
+// "gemm_split" knob (default 1): float32 models run layer 1's feature transform on the bfloat16 matrix instruction
+// with three-plane operands.
+bool want_l1_split(int dtype) { return dtype == GCN_F32 && tunable("gemm_split", 1) != 0; }
 
 // Layer widths: 1..16 layers; the input may be up to 4096 wide; hidden and output widths are limited to what one
 // aggregation launch covers with a wave per row (64 lanes x 16 bytes): 256 columns in float32, 512 in bfloat16.
@@ -838,6 +852,7 @@ int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_
     m.dtype = dtype;
     m.L = n_layers;
     m.l1_cached = want_l1_cached(n_layers, dims);
+    m.l1_split = want_l1_split(dtype);
     for (int l = 0; l < n_layers; ++l)
         m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
@@ -885,6 +900,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     m->p = dropout_p;
     m->seed = seed;
     m->l1_cached = want_l1_cached(n_layers, dims);
+    m->l1_split = want_l1_split(dtype);
     for (int l = 0; l < n_layers; ++l)
         m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
@@ -909,6 +925,10 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
                                    g->ldf, cols, g->f, kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums);
             rc = spmm_launch(a, st);
         }
+    }
+    if (!rc && m->l1_split) {
+        const float *src = (const float *)(m->l1_cached ? m->pax : g->x);
+        rc = pack_rows(src, g->ldf, g->n, g->ldf, m->sp_a, true, st);
     }
     if (rc) {
         delete m;
@@ -1003,6 +1023,19 @@ int gcn_get_tensor(gcn_model *m, int which, int layer, float *dst, size_t dst_fl
     return unpad_rows(src, src_dtype, ld, rows, cols, dst, rowdiv, st);
 }
 
+namespace {
+
+// c = act(rowscale * (A W_1)) with A = X or P from its packed form; W_1^T is packed first
+int l1_split_forward(gcn_model *m, float *c, const float *rowscale, const Activation *act, hipStream_t st,
+                     const PlaneSink *sink = nullptr) {
+    const Layer &ly = m->layers[0];
+    int rc = pack_transposed(ly.w, ly.ld_out, ly.ld_in, ly.ld_out, m->sp_wt, false, st);
+    if (rc) return rc;
+    return gemm_split(m->sp_a, m->sp_wt, c, ly.ld_out, m->g->n, ly.ld_in, ly.ld_out, rowscale, act, st, sink);
+}
+
+}  // namespace
+
 int gcn_forward(gcn_model *m, int training, void *stream) {
     if (!m) {
         set_error("gcn_forward: null model");
@@ -1027,6 +1060,8 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
             const int t_nn = timing_open(kTimeGemmNN, ly.d_out, st);
             int rc = bf ? gemm_bf16_nn(m->pax, g->ldf, ly.wbt, ly.ld_in, ly.h, ly.ld_out, g->n, ly.ld_in, ly.ld_out, nullptr,
                                        &act, st)
+                     : m->l1_split
+                        ? l1_split_forward(m, (float *)ly.h, nullptr, &act, st)
                         : gemm_nn((const float *)m->pax, g->ldf, ly.w, ly.ld_out, (float *)ly.h, ly.ld_out, g->n, ly.ld_in,
                                   ly.ld_out, nullptr, &act, st);
             timing_close(t_nn, st);
@@ -1035,17 +1070,21 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
             ld_prev = ly.ld_out;
             continue;
         }
-        // T = D^-1/2 (H_{l-1} W_l)
+        // Z = A_hat-aggregate(T), T = D^-1/2 (H_{l-1} W_l); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits
+        // stay float.  The product also leaves T in the form the aggregation's tile product reads, when it runs one.
+        SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
+                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums);
+        const PlaneSink sink = tiles_plane_sink(a);
+        a.planes_ready = sink.planes != nullptr;
         const int t_nn = timing_open(kTimeGemmNN, ly.d_out, st);
         int rc = bf ? gemm_bf16_nn(h_prev, ld_prev, ly.wbt, ly.ld_in, ly.t, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
                                    g->pb.dinv, nullptr, st)
+                 : (l == 1 && m->l1_split)
+                    ? l1_split_forward(m, (float *)ly.t, g->pb.dinv, nullptr, st, &sink)
                     : gemm_nn((const float *)h_prev, ld_prev, ly.w, ly.ld_out, (float *)ly.t, ly.ld_out, g->n, ly.ld_in,
-                              ly.ld_out, g->pb.dinv, nullptr, st);
+                              ly.ld_out, g->pb.dinv, nullptr, st, &sink);
         timing_close(t_nn, st);
         if (rc) return rc;
-        // Z = A_hat-aggregate(T); hidden layers: H = relu(Z) [* keep / (1 - p)]; the logits stay float
-        SpmmArgs a = spmm_args(g, ly.t, m->dtype, ly.ld_out, ly.h, l < m->L ? m->dtype : GCN_F32, ly.ld_out, ly.ld_out,
-                               ly.d_out, l < m->L ? kEpiRelu : kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums);
         a.drop_threshold = act.drop_threshold;
         a.keep_scale = act.keep_scale;
         a.drop_key = act.drop_key;
@@ -1107,6 +1146,7 @@ int gcn_backward(gcn_model *m, void *stream) {
     const gcn_graph *g = m->g;
     const float keep_scale = m->trained_forward ? (float)(1.0 / (1.0 - (double)m->p)) : 1.0f;
     const bool bf = m->dtype == GCN_BF16;
+    bool planes_ready = false;   // the product that wrote this layer's dZ also left it as the tile product's planes
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
         if (l == 1 && m->l1_cached) {
@@ -1131,6 +1171,8 @@ int gcn_backward(gcn_model *m, void *stream) {
         // (the rows of dZ_L outside the train mask are zero: the loss kernel writes them so)
         SpmmArgs a = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out, kEpiNone,
                                m->tile_sums, m->chunk_sums, m->gather_sums, l == m->L);
+        a.planes_ready = planes_ready;
+        planes_ready = false;
         int rc = spmm_launch(a, st);
         if (rc) return rc;
         // dW_l = H_{l-1}^T G
@@ -1151,12 +1193,20 @@ int gcn_backward(gcn_model *m, void *stream) {
         if (l > 1) {
             // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
             Layer &lp = m->layers[l - 2];
-            const float *next_scale = (l == 2 && m->l1_cached) ? nullptr : g->pb.dinv;   // no aggregation follows
+            const bool aggregated = !(l == 2 && m->l1_cached);
+            const float *next_scale = aggregated ? g->pb.dinv : nullptr;
+            PlaneSink sink{nullptr, 0, 0};
+            if (aggregated) {   // the same arguments as the aggregation of the next round of this loop
+                const SpmmArgs next = spmm_args(g, lp.dzs, m->dtype, lp.ld_out, lp.g, m->dtype, lp.ld_out, lp.ld_out,
+                                                lp.d_out, kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums, false);
+                sink = tiles_plane_sink(next);
+                planes_ready = sink.planes != nullptr;
+            }
             const int t_nt = timing_open(kTimeGemmNT, lp.d_out, st);
             rc = bf ? gemm_bf16_nt(ly.g, ly.ld_out, ly.wb, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out,
                                    next_scale, lp.h, lp.ld_out, keep_scale, st)
                     : gemm_nt((const float *)ly.g, ly.ld_out, ly.w, ly.ld_out, (float *)lp.dzs, lp.ld_out, g->n,
-                              ly.ld_out, lp.ld_out, next_scale, (const float *)lp.h, lp.ld_out, keep_scale, st);
+                              ly.ld_out, lp.ld_out, next_scale, (const float *)lp.h, lp.ld_out, keep_scale, st, &sink);
             timing_close(t_nt, st);
             if (rc) return rc;
         }

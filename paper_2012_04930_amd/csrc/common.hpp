@@ -49,7 +49,7 @@ constexpr int kColBlocks = kXcds * kRangesPerXcd;
 constexpr int kTileRows = 128;             // a dense tile covers this many rows by 32 columns
 constexpr int kTileMinEntriesFloor = 64;   // a dense tile holds at least this many entries (bounds their number)
 constexpr int kTileMinEntriesDefault = 64; // the break-even of one tile product against gathering its entries
-constexpr int kTileRunMin = 32;            // a row block with up to 1.5 x this many tiles is never cut into runs
+constexpr int kTileRunMin = 16;            // a row block with up to 1.5 x this many tiles is never cut into runs
 constexpr int kTileChunkMin = 8;           // runs are no shorter than this
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -260,7 +260,18 @@ struct SpmmArgs {
     hipStream_t side;
     hipEvent_t ev_fork, ev_join;
     int finish_mode;     // set by spmm_launch, see SpmmFinish
+    int planes_ready;    // tile_planes already holds this input (its producer wrote it through a PlaneSink)
 };
+// Where the producer of an aggregation's float32 input also leaves it as the tile product's operand planes
+// (planes == nullptr: nowhere); n_ct blocks of 32 rows, `ld` 16-byte units per block and k-octet.
+struct PlaneSink {
+    void *planes;
+    int n_ct;
+    int ld;
+};
+// the sink for aggregation `a` (knob "fused_planes", default 1), or none when that aggregation runs no tile product
+// over float32 input
+PlaneSink tiles_plane_sink(const SpmmArgs &a);
 // what the gather kernels do with a row's sum
 enum SpmmFinish {
     kFinishRow = 0,      // scale by d_i^-1/2, activation, store
@@ -278,10 +289,13 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st);
 //   nn:  c[m, :] = act(rowscale[m] * (a[m, :] b))           a: M x K,  b: K x N,  c: M x N
 //   nt:  c[m, :] = rowscale[m] * scale * [gate[m, :] > 0] * (a[m, :] b^T)      b: N x K
 //   tn:  c = a^T b  reduced over the M rows of a and b in fixed order (split over row ranges)
+// nn and nt also leave their output in *sink when one is given (plane_sink.hpp)
 int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, const Activation *act /* may be null */, hipStream_t st);
+            const float *rowscale, const Activation *act /* may be null */, hipStream_t st,
+            const PlaneSink *sink = nullptr);
 int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st);
+            const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st,
+            const PlaneSink *sink = nullptr);
 // nn for few rows: c = [relu](a b) with the shared dimension split over workgroups and the partial matrices added
 // in ascending order; partials holds gemm_nn_splitk_partial_floats(M, K, N) floats
 size_t gemm_nn_splitk_partial_floats(int64_t M, int K, int N);
@@ -302,6 +316,19 @@ int gemm_bf16_nt(const void *a, int lda, const void *b, int ldb, void *c, int ld
 size_t gemm_bf16_tn_partial_floats(int64_t rows, int M, int N);
 int gemm_bf16_tn_partials(const void *a, int lda, const void *b, int ldb, int ldc, int64_t rows, int M, int N,
                           float *partials, size_t partial_floats, int *splits_out, hipStream_t st);
+
+// float32 products on the bfloat16 matrix instruction (gemm_split.hip).  A "packed" operand holds a float32 matrix
+// [rows x k] in the order the instruction's lanes read it, padded with zeros to whole tiles of 32 rows and 32
+// shared indices: the left operand of a product as float32 (split into three bfloat16 planes in registers), the
+// right operand as the three planes; packed_bytes(rows, k, left) bytes.
+size_t packed_bytes(int64_t rows, int64_t k, bool left);
+// the operand whose rows are src's rows (src [rows x cols], shared index = column)
+int pack_rows(const float *src, int ld, int64_t rows, int cols, void *dst, bool left, hipStream_t st);
+// the operand whose rows are src's columns (shared index = src's row)
+int pack_transposed(const float *src, int ld, int64_t rows, int cols, void *dst, bool left, hipStream_t st);
+// c [M x N] = act(rowscale * (a b^T)), a [M x K] packed left, b [N x K] packed right
+int gemm_split(const void *a, const void *b, float *c, int ldc, int64_t M, int64_t K, int N, const float *rowscale,
+               const Activation *act /* may be null */, hipStream_t st, const PlaneSink *sink = nullptr);
 
 // ---------------------------------------------------------------------------------------------
 // Event timing of launches (api.hip): timing_open records an event on the stream the work is about to be launched

@@ -13,6 +13,7 @@
 // k = 8 h + s at step s, so the A fragment is two 16-byte LDS reads.
 #include "common.hpp"
 #include "epilogue.hpp"
+#include "plane_sink.hpp"
 
 namespace gcn {
 
@@ -44,6 +45,7 @@ struct GemmArgs {
     Activation act;          // nn: applied after the row scale
     int k_per_split;         // nn: 0 = the whole shared dimension in one workgroup; else blockIdx.y takes this many k
                              // and writes its own partial matrix (M x ldc, one after the other at c)
+    PlaneSink sink;          // nn without split, nt: the output once more, as the tile product's operand planes
 };
 
 template <int MODE, int WM, int WN, int TN>
@@ -192,14 +194,17 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
     float *cbase = g.c;
     if (MODE == kTN) cbase += (int64_t)blockIdx.y * (int64_t)g.K * g.ldc;   // this split's partial matrix
     if (MODE == kNN && g.k_per_split > 0) cbase += (int64_t)blockIdx.y * g.M * g.ldc;
+    const bool to_sink = MODE != kTN && g.sink.planes && !(MODE == kNN && g.k_per_split > 0);
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int col = n0 + (wn * TN + t) * 32 + l32;
+        float xs[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t row = m0 + wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            float x = 0.0f;
             if (row < out_rows && col < g.ldc) {
-                float x = acc[t][v];
+                x = acc[t][v];
                 if (MODE == kNN) {
                     if (g.rowscale) x *= g.rowscale[row];
                     x = activate(x, g.act, row, col);
@@ -210,7 +215,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
                 }
                 cbase[row * g.ldc + col] = x;
             }
+            xs[v] = x;
         }
+        if (to_sink) sink_store(g.sink, m0 + wm * 32, col, h, xs);
     }
 }
 
@@ -332,13 +339,14 @@ bool check_ld(int lda, int ldb, int ldc) { return lda % 16 == 0 && ldb % 16 == 0
 }  // namespace
 
 int gemm_nn(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, const Activation *act, hipStream_t st) {
+            const float *rowscale, const Activation *act, hipStream_t st, const PlaneSink *sink) {
     if (M <= 0) return GCN_OK;
     if (!check_ld(lda, ldb, ldc) || K % BK != 0 || K > lda || N > ldb) {
         set_error("gemm_nn: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0, act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, nullptr, 0, 1.0f, 0, act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0,
+               sink ? *sink : PlaneSink{nullptr, 0, 0}};
     return launch_rows<kNN>(g, st);
 }
 
@@ -370,7 +378,7 @@ int gemm_nn_splitk(const float *a, int lda, const float *b, int ldb, float *c, i
     }
     int per = (K + splits - 1) / splits;
     per = (per + BK - 1) / BK * BK;
-    GemmArgs g{a, lda, b, ldb, partials, ldc, M, K, N, nullptr, nullptr, 0, 1.0f, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, per};
+    GemmArgs g{a, lda, b, ldb, partials, ldc, M, K, N, nullptr, nullptr, 0, 1.0f, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, per, PlaneSink{nullptr, 0, 0}};
     const int ntiles = (N + 127) / 128;
     const unsigned gx = (unsigned)((M + 63) / 64) * ntiles;
     k_gemm<kNN, 2, 2, 2><<<dim3(gx, (unsigned)splits), dim3(kThreads), 0, st>>>(g);
@@ -383,13 +391,14 @@ int gemm_nn_splitk(const float *a, int lda, const float *b, int ldb, float *c, i
 }
 
 int gemm_nt(const float *a, int lda, const float *b, int ldb, float *c, int ldc, int64_t M, int K, int N,
-            const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st) {
+            const float *rowscale, const float *gate, int ldg, float scale, hipStream_t st, const PlaneSink *sink) {
     if (M <= 0) return GCN_OK;
     if (!check_ld(lda, ldb, ldc) || K % BK != 0 || K > lda || K > ldb || (gate && ldg < ldc)) {
         set_error("gemm_nt: bad shape M=%lld K=%d N=%d lda=%d ldb=%d ldc=%d", (long long)M, K, N, lda, ldb, ldc);
         return GCN_EINVAL;
     }
-    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
+    GemmArgs g{a, lda, b, ldb, c, ldc, M, K, N, rowscale, gate, ldg, scale, 0, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0,
+               sink ? *sink : PlaneSink{nullptr, 0, 0}};
     return launch_rows<kNT>(g, st);
 }
 
@@ -412,7 +421,8 @@ int gemm_tn(const float *a, int lda, const float *b, int ldb, float *c, int ldc,
     }
     int64_t per = (rows + splits - 1) / splits;
     per = (per + BK - 1) / BK * BK;
-    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0};
+    GemmArgs g{a, lda, b, ldb, partials, ldc, rows, M, N, nullptr, nullptr, 0, 1.0f, per, Activation{kActNone, 0, 0u, 1.0f, 0ull}, 0,
+               PlaneSink{nullptr, 0, 0}};
     const int mtiles = (M + 127) / 128;
     if (N > 64) {
         const int ntiles = (N + 127) / 128;

@@ -27,6 +27,7 @@
 
 #include "common.hpp"
 #include "dtypes.hpp"
+#include "bf16_split.hpp"
 
 namespace gcn {
 
@@ -174,11 +175,6 @@ __global__ __launch_bounds__(kThreads) void k_residual(int64_t n, const int64_t 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 
-// two bfloat16 (the upper halves of two float32 encodings) in one word: a in the low half, b in the high half
-__device__ inline uint32_t pack_upper(uint32_t a, uint32_t b) {
-    return __builtin_amdgcn_perm(b, a, 0x07060302u);   // bytes 2, 3 of a below bytes 2, 3 of b: one instruction
-}
-
 template <typename TIn>
 struct Planes;
 template <>
@@ -200,47 +196,6 @@ __device__ inline void load_pair(const bf16_t *p, uint32_t (&v)[2]) {
     const uint32_t q = *reinterpret_cast<const uint32_t *>(p);
     v[0] = q << 16;
     v[1] = q & 0xffff0000u;
-}
-
-// Eight float32 encodings x[0..8) (consecutive rows of one column) -> `planes` operands of eight bfloat16 each:
-// plane 0 the values with the low 16 bits cleared, plane 1 the same of what is left, plane 2 the rest (exact).
-template <int PLANES>
-__device__ inline void split_column(const uint32_t (&x)[8], uint4 (&out)[PLANES]) {
-    uint32_t hi[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) hi[q] = pack_upper(x[2 * q], x[2 * q + 1]);
-    out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    if (PLANES > 1) {
-        uint32_t r1[8], r2[8], mid[4], lo[4];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            r1[i] = __float_as_uint(__uint_as_float(x[i]) - __uint_as_float(x[i] & 0xffff0000u));
-            r2[i] = __float_as_uint(__uint_as_float(r1[i]) - __uint_as_float(r1[i] & 0xffff0000u));
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            mid[q] = pack_upper(r1[2 * q], r1[2 * q + 1]);
-            lo[q] = pack_upper(r2[2 * q], r2[2 * q + 1]);
-        }
-        out[1] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
-        out[PLANES - 1] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    }
-}
-
-// Bits sh .. sh + 7 of w -> eight bfloat16 ones and zeros (bit sh + i -> element i).
-__device__ inline bf16x8 expand_bits(uint32_t w, int sh) {
-    const uint32_t byte = (w >> sh) & 0xffu;
-    const uint32_t z = byte | (byte << 15);   // even bits stay in the low half, odd bits land in the high half
-    union {
-        uint32_t u[4];
-        bf16x8 v;
-    } r;
-    // bit 2q of z -> 0x3F80 (bfloat16 one) in the low half, bit 2q + 16 -> the same in the high half
-    r.u[0] = __umul24(z & 0x00010001u, 0x3F80u);
-    r.u[1] = __umul24(z & 0x00040004u, 0x0FE0u);
-    r.u[2] = __umul24(z & 0x00100010u, 0x03F8u);
-    r.u[3] = __umul24(z & 0x00400040u, 0x00FEu);
-    return r.v;
 }
 
 // ---- step 1: the input in the order the matrix instruction reads its second operand.
@@ -506,9 +461,11 @@ int tiles_build(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_
 int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_t st) {
     const int64_t n_rb = (int64_t)tile_ptr.size() - 1;
     const int64_t total = tile_ptr[n_rb];
-    constexpr int64_t kSlots = 512;   // two workgroups on each of 256 compute units (register use of k_tiles)
+    int64_t kSlots = tunable("tile_slots", 768);   // workgroups of k_tiles the chip is taken to hold at a time
+    if (kSlots < 256) kSlots = 256;
     int64_t run = (total + kSlots - 1) / kSlots;
-    if (run < kTileRunMin) run = kTileRunMin;
+    const int64_t run_min = tunable("tile_run_min", kTileRunMin);
+    if (run < run_min) run = run_min;
     int64_t chunk = tunable("tile_chunk", 0);
     if (chunk <= 0) chunk = run / 2;
     if (chunk < kTileChunkMin) chunk = kTileChunkMin;
@@ -588,6 +545,12 @@ size_t tiles_plane_bytes(int64_t n, int cols, int dtype) {
     return (size_t)(dtype == GCN_BF16 ? 1 : 3) * n_ct * 4 * (size_t)round_up(cols, 32) * 16;
 }
 
+PlaneSink tiles_plane_sink(const SpmmArgs &a) {
+    if (!a.tile_ptr || !a.tile_planes || a.t_dtype != GCN_F32 || a.cols > 256 || tunable("fused_planes", 1) == 0)
+        return PlaneSink{nullptr, 0, 0};
+    return PlaneSink{a.tile_planes, (int)((a.n + 31) / 32), (int)round_up(a.cols, 32)};
+}
+
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     if (a.cols > 256 || a.n_items < 1 || (a.n_slots > 0 && !a.tile_partial) || !a.tile_planes) {
         set_error("dense tiles: at most 256 columns, a buffer for the operand planes, and one for partial sums when runs were cut");
@@ -597,8 +560,10 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     const int ld = (int)round_up(a.cols, 32);
     uint4 *planes = static_cast<uint4 *>(a.tile_planes);
     const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
-    const int t_planes = timing_open(kTimePlanes, a.width, st);
-    if (a.t_dtype == GCN_BF16)
+    const int t_planes = a.planes_ready ? -1 : timing_open(kTimePlanes, a.width, st);
+    if (a.planes_ready) {
+        // the input's producer wrote the planes
+    } else if (a.t_dtype == GCN_BF16)
         k_tile_planes<bf16_t><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
             static_cast<const bf16_t *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
     else
