@@ -279,7 +279,9 @@ enum SpmmFinish {
     kFinishPlainSum = 2    // store the plain sum (float32 output); a later launch finishes the rows
 };
 size_t tiles_plane_bytes(int64_t n, int cols, int dtype);
-// dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling)
+// the aggregation's input as the tile product's operand planes, unless its producer has written them
+int tiles_planes(const SpmmArgs &a, hipStream_t st);
+// dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling); after tiles_planes
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);
 

@@ -589,6 +589,13 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     // "spmm_tiles_first": the other way round; measured the same on the benchmark partition, where both kernels
     // slow each other down through the bytes they pull from the L2s: 254 us together against 195 + 98 us alone).
     hipStream_t gather_stream = st;
+    // the pass that lays the input out for the tile product runs before the two part: beside the gather it takes
+    // three times as long, at the head of the longer of the two paths
+    if (a.tile_ptr) rc = tiles_planes(a, st);
+    if (rc != GCN_OK) {
+        timing_close(t_all, st);
+        return rc;
+    }
     if (a.tile_ptr && overlap) {
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
         if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");

@@ -551,6 +551,30 @@ PlaneSink tiles_plane_sink(const SpmmArgs &a) {
     return PlaneSink{a.tile_planes, (int)((a.n + 31) / 32), (int)round_up(a.cols, 32)};
 }
 
+// the input of aggregation `a` as the product's operand planes (nothing to do when its producer wrote them)
+int tiles_planes(const SpmmArgs &a, hipStream_t st) {
+    if (a.planes_ready) return GCN_OK;
+    if (a.cols > 256 || !a.tile_planes) {
+        set_error("dense tiles: at most 256 columns and a buffer for the operand planes");
+        return GCN_EINVAL;
+    }
+    const int n_ct = (int)((a.n + 31) / 32);
+    const int ld = (int)round_up(a.cols, 32);
+    uint4 *planes = static_cast<uint4 *>(a.tile_planes);
+    const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
+    const int t_planes = timing_open(kTimePlanes, a.width, st);
+    if (a.t_dtype == GCN_BF16)
+        k_tile_planes<bf16_t><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
+            static_cast<const bf16_t *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
+    else
+        k_tile_planes<float><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
+            static_cast<const float *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
+    GCN_LAUNCH_CHECK();
+    timing_close(t_planes, st);
+    return GCN_OK;
+}
+
+// (after tiles_planes, on a stream ordered behind it)
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     if (a.cols > 256 || a.n_items < 1 || (a.n_slots > 0 && !a.tile_partial) || !a.tile_planes) {
         set_error("dense tiles: at most 256 columns, a buffer for the operand planes, and one for partial sums when runs were cut");
@@ -559,18 +583,6 @@ int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     const int n_ct = (int)((a.n + 31) / 32);
     const int ld = (int)round_up(a.cols, 32);
     uint4 *planes = static_cast<uint4 *>(a.tile_planes);
-    const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
-    const int t_planes = a.planes_ready ? -1 : timing_open(kTimePlanes, a.width, st);
-    if (a.planes_ready) {
-        // the input's producer wrote the planes
-    } else if (a.t_dtype == GCN_BF16)
-        k_tile_planes<bf16_t><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
-            static_cast<const bf16_t *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
-    else
-        k_tile_planes<float><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(
-            static_cast<const float *>(a.t), a.ld_t, a.n, n_ct, a.cols, ld, planes);
-    GCN_LAUNCH_CHECK();
-    timing_close(t_planes, st);
     const int t_tiles = timing_open(kTimeTiles, a.width, st);
     const TileItem *items = reinterpret_cast<const TileItem *>(a.tile_items);
 #define GCN_TILES(NBLK)                                                                                               \
