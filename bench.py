@@ -291,8 +291,8 @@ def main() -> int:
         ceil = ceilings(B, torch, n + 1, (w_top + 15) // 16 * 16 * esize // 4)
         # the dominant kernel: the one with the most time per epoch among the parts (not the wholes)
         parts = {k: v for k, v in kernels.items() if not k.startswith("aggregation.")}
-        if parts:
-            dom = max(parts, key=lambda k: parts[k]["ms_per_epoch"])
+
+        def roofline_of(dom):
             kind, w = dom.split(".w")
             w = int(w)
             avg = parts[dom]["avg_ms"]
@@ -307,33 +307,33 @@ def main() -> int:
                 cached = (n + 1) * ld * esize <= (256 << 20)
                 peak = ceil["gather_l2_hits_GBps"] if cached else HBM_PEAK_GBS
                 traffic = read_traffic(wl.name, "gather", w) if args.dtype is None else None
-                roofline = {"bound": "cache" if cached else "hbm", "kernel": "k_spmm_phased | k_spmm_wave + k_spmm_group: gather over the "
-                            + ("%d entries outside the dense tiles" % E_res if tile_info["in_use"] else "whole pattern")
-                            + ", width %d" % w,
-                            "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s",
-                            "frac": round(achieved / peak, 4),
-                            "peak_is": ("gather ceiling measured in this run: every gather an L2 hit, table of the "
-                                        "aggregated matrix's size (gcn_ceiling_gather)") if cached else
-                                       "HBM peak: the gathered matrix is larger than the last-level cache",
-                            "bytes_per_launch": by, "avg_launch_ms": avg,
-                            "traffic": (traffic["fetch_bytes"] + traffic["write_bytes"]) if traffic else None,
-                            "traffic_detail": traffic,
-                            "hbm_frac": round((traffic["fetch_bytes"] + traffic["write_bytes"]) / avg / 1e6 / HBM_PEAK_GBS, 4)
-                            if traffic else None,
-                            "compulsory_GBps": round(compulsory_bytes(E_res, n, ld, esize) / avg / 1e6, 1),
-                            "alu_frac_fp32": round(2.0 * E_res * w / (avg * 1e-3) / (FP32_PEAK_TFLOPS * 1e12), 4),
-                            "frac_of_no_locality_ceiling": round(achieved / ceil["gather_no_locality_GBps"], 4)}
-            elif kind == "tiles":
+                return {"bound": "cache" if cached else "hbm", "kernel": "k_spmm_phased | k_spmm_wave + k_spmm_group: gather over the "
+                        + ("%d entries outside the dense tiles" % E_res if tile_info["in_use"] else "whole pattern")
+                        + ", width %d" % w,
+                        "achieved": round(achieved, 1), "peak": peak, "unit": "GB/s",
+                        "frac": round(achieved / peak, 4),
+                        "peak_is": ("gather ceiling measured in this run: every gather an L2 hit, table of the "
+                                    "aggregated matrix's size (gcn_ceiling_gather)") if cached else
+                                   "HBM peak: the gathered matrix is larger than the last-level cache",
+                        "bytes_per_launch": by, "avg_launch_ms": avg,
+                        "traffic": (traffic["fetch_bytes"] + traffic["write_bytes"]) if traffic else None,
+                        "traffic_detail": traffic,
+                        "hbm_frac": round((traffic["fetch_bytes"] + traffic["write_bytes"]) / avg / 1e6 / HBM_PEAK_GBS, 4)
+                        if traffic else None,
+                        "compulsory_GBps": round(compulsory_bytes(E_res, n, ld, esize) / avg / 1e6, 1),
+                        "alu_frac_fp32": round(2.0 * E_res * w / (avg * 1e-3) / (FP32_PEAK_TFLOPS * 1e12), 4),
+                        "frac_of_no_locality_ceiling": round(achieved / ceil["gather_no_locality_GBps"], 4)}
+            if kind == "tiles":
                 planes = 1 if dtype == B.GCN_BF16 else 3
                 flops = tile_info["n_tiles"] * planes * 2.0 * 128 * 32 * ((w + 31) // 32 * 32)
                 achieved = flops / (avg * 1e-3) / 1e12
-                roofline = {"bound": "mfma", "kernel": "k_tiles: %d dense tiles of 128 x 32, %d bfloat16 plane(s), "
-                            "width %d" % (tile_info["n_tiles"], planes, w),
-                            "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                            "flops_per_launch": flops, "avg_launch_ms": avg,
-                            "frac_of_measured_mfma_ceiling": round(achieved / ceil["mfma_bf16_32x32x16_TFLOPs"], 4)}
-            elif kind.startswith("gemm"):
+                return {"bound": "mfma", "kernel": "k_tiles: %d dense tiles of 128 x 32, %d bfloat16 plane(s), "
+                        "width %d" % (tile_info["n_tiles"], planes, w),
+                        "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                        "flops_per_launch": flops, "avg_launch_ms": avg,
+                        "frac_of_measured_mfma_ceiling": round(achieved / ceil["mfma_bf16_32x32x16_TFLOPs"], 4)}
+            if kind.startswith("gemm"):
                 # dense products on the float32 (or bfloat16) matrix instruction: flops of the layers of this width
                 ls = [l for l in range(1, len(wl.dims)) if wl.dims[l] == w] if kind != "gemm_nt" else \
                      [l for l in range(1, len(wl.dims) - 1) if wl.dims[l] == w]
@@ -342,13 +342,22 @@ def main() -> int:
                 flops = sum(fl) / max(len(fl), 1)
                 peak = BF16_MFMA_PEAK_TFLOPS if dtype == B.GCN_BF16 else FP32_PEAK_TFLOPS
                 achieved = flops / (avg * 1e-3) / 1e12
-                roofline = {"bound": "mfma", "kernel": "k_gemm (%s), output width %d" % (kind, w),
-                            "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                            "frac": round(achieved / peak, 4), "traffic": None, "flops_per_launch": flops,
-                            "avg_launch_ms": avg}
-            else:
-                roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": None, "traffic": None, "avg_launch_ms": avg}
+                return {"bound": "mfma", "kernel": "k_gemm (%s), output width %d" % (kind, w),
+                        "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                        "frac": round(achieved / peak, 4), "traffic": None, "flops_per_launch": flops,
+                        "avg_launch_ms": avg}
+            return {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": None, "traffic": None, "avg_launch_ms": avg}
+
+        if parts:
+            dom = max(parts, key=lambda k: parts[k]["ms_per_epoch"])
+            roofline = roofline_of(dom)
+            # the tile product and the gather of one aggregation run side by side on two streams: each one's time is
+            # taken while it shares the chip with the other, so the other one's position is given as well
+            kind, w = dom.split(".w")
+            beside = {"tiles": "gather", "gather": "tiles"}.get(kind)
+            if beside and "%s.w%s" % (beside, w) in parts:
+                roofline["runs_beside"] = roofline_of("%s.w%s" % (beside, w))
 
     default_cached = wl.dims[0] <= wl.dims[1] and len(wl.dims) > 2
     other = None

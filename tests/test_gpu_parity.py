@@ -420,6 +420,38 @@ def test_first_layer_from_cached_aggregate(B, oracle, case, dtype_name):
     assert results[0]["G"][0] is not None and results[2]["G"][0] is None
 
 
+# ------------------------------------------------------------------ layer 1's product on the bfloat16 instruction
+@pytest.mark.parametrize("cache_ax", [0, 2])
+def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, cache_ax):
+    """Layer 1's feature transform from packed three-plane operands ("gemm_split") against the float32 matrix
+    instruction: both within the bar of the oracle, and within 1e-5 of each other.  The operand planes that the
+    dense products write for the tile product ("fused_planes") are bit for bit what the separate pass writes, so
+    every tensor of the epoch is identical with and without.  A partition with dense tiles, 602 input columns
+    (19 k-blocks, the last one padded), dropout on."""
+    wl = workloads.reddit_partition(scale=0.12)
+    g = H.gpu_graph(B, wl)
+    assert B.gcn_graph_tile_info(g)["in_use"]
+    runs = {}
+    try:
+        for split, fused in ((1, 1), (0, 1), (1, 0)):
+            B.gcn_set_tunable("gemm_split", split)
+            B.gcn_set_tunable("fused_planes", fused)
+            _, runs[(split, fused)] = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
+    finally:
+        B.gcn_set_tunable("gemm_split", 1)
+        B.gcn_set_tunable("fused_planes", 1)
+    for key, gpu in runs.items():
+        _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=0.25, seed=5)
+        H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
+    a, b, c = runs[(1, 1)], runs[(0, 1)], runs[(1, 0)]
+    for name in ("H", "dW", "W"):
+        for x, y, z in zip(a[name], b[name], c[name]):
+            np.testing.assert_array_equal(x, z)                                  # planes from the epilogue or not
+            scale = float(np.sqrt(np.mean(np.square(y.astype(np.float64))))) + 1e-30
+            assert float(np.max(np.abs(x.astype(np.float64) - y))) <= 1e-5 * scale * 8.0, name
+    np.testing.assert_array_equal(a["logits"], c["logits"])
+
+
 # ------------------------------------------------------------------ Adam
 def test_adam_update_kernel_matches_oracle(B, oracle):
     count = 100_003
