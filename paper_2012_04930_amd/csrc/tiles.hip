@@ -199,12 +199,13 @@ __device__ inline void load_pair(const bf16_t *p, uint32_t (&v)[2]) {
 }
 
 // ---- step 1: the input in the order the matrix instruction reads its second operand.
-// planes[p][ct][kg][c] is one 16-byte unit: the bfloat16 values of plane p of t[32 ct + 8 kg + 0 .. 7, c], i.e. the
-// eight consecutive-k values of one k-octet of one column (p, ct, kg, c major to minor; c < ld).  Rows at or past n
-// and columns at or past `cols` are zero (ld, the planes' own leading dimension, is cols rounded up to whole blocks
-// of 32).  One thread per (ct, kg, pair of columns): eight rows of two columns in, two units per plane out; the
-// conversion's arithmetic runs here, in a kernel bound by memory, so the product below is left with (almost)
-// nothing but matrix instructions.
+// A unit holds t[32 ct + 8 kg + 0 .. 7, c], the eight consecutive-k values of one k-octet of one column, units
+// ordered (ct, kg, c) major to minor, c < ld.  bfloat16 input: 16 bytes per unit, units[(ct * 4 + kg) * ld + c].
+// float32 input: the eight float32 values as two 16-byte halves (rows 0 .. 3 and 4 .. 7 of the octet),
+// units[((ct * 4 + kg) * 2 + half) * ld + c]; the product splits them into three bfloat16 planes in registers (the
+// same 4 bytes per element through the caches as the matrix itself, where three stored planes would be 6).
+// Rows at or past n and columns at or past `cols` are zero (ld, the units' own leading dimension, is cols rounded
+// up to whole blocks of 32).  One thread per (ct, kg, pair of columns): eight rows of two columns in, two units out.
 template <typename TIn>
 __global__ __launch_bounds__(kThreads) void k_tile_planes(const TIn *__restrict__ t, int ld_t, int64_t n, int n_ct,
                                                           int cols, int ld, uint4 *__restrict__ planes) {
@@ -222,16 +223,20 @@ __global__ __launch_bounds__(kThreads) void k_tile_planes(const TIn *__restrict_
         r[k][0] = r[k][1] = 0u;
         if (row0 + k < n && 2 * c2 < cols) load_pair(t + (row0 + k) * ld_t + 2 * c2, r[k]);   // cols is even
     }
-    const size_t plane_units = (size_t)n_ct * 4 * ld;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-        uint32_t x[8];
+        if (P == 1) {
+            uint32_t x[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) x[k] = r[k][c];
-        uint4 o[P];
-        split_column<P>(x, o);
-#pragma unroll
-        for (int p = 0; p < P; ++p) planes[p * plane_units + ((size_t)ct * 4 + kg) * ld + 2 * c2 + c] = o[p];
+            for (int k = 0; k < 8; ++k) x[k] = r[k][c];
+            uint4 o[1];
+            split_column<1>(x, o);
+            planes[((size_t)ct * 4 + kg) * ld + 2 * c2 + c] = o[0];
+        } else {
+            uint4 *unit = planes + ((size_t)ct * 4 + kg) * 2 * ld + 2 * c2 + c;
+            unit[0] = make_uint4(r[0][c], r[1][c], r[2][c], r[3][c]);
+            unit[ld] = make_uint4(r[4][c], r[5][c], r[6][c], r[7][c]);
+        }
     }
 }
 
@@ -279,12 +284,13 @@ __global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__
     if (col - l32 >= cols) return;                 // the whole wave: nothing of its block is inside the matrix
     const int64_t first = item.first;
     const int count = item.count;
-    const size_t plane_units = (size_t)n_ct * 4 * ld;
-    // unit of (plane p, k-step s) for this lane inside tile ct:  p * plane_units + ct * 4 * ld + (2 s + h) * ld + col
-    const uint32_t lane_unit = (uint32_t)(h * ld + col);   // col < ld: the planes hold whole blocks of 32 columns
+    // pieces of 16 bytes per unit: one (bfloat16 input) or two (float32 input, split below)
+    constexpr int Q = P == 1 ? 1 : 2;
+    // piece q of k-step s for this lane inside tile ct:  (ct * 4 + 2 s + h) * Q * ld + q * ld + col
+    const uint32_t lane_unit = (uint32_t)(h * Q * ld + col);   // col < ld: the units cover whole blocks of 32 columns
 
     struct Stage {
-        uint4 b[2][P];
+        uint4 b[2][Q];
         uint32_t w[SUB];
     };
     // Loads of tile i (clamped into the run, so they are always valid).  The tile's column index was fetched by the
@@ -294,11 +300,11 @@ __global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__
         const int64_t ti = first + (i < count ? i : count - 1);
         const int ct = ct_next;
         ct_next = tile_col[first + (i + 1 < count ? i + 1 : count - 1)];
-        const uint4 *base = planes + (size_t)ct * 4 * ld;   // wave-uniform
+        const uint4 *base = planes + (size_t)ct * 4 * Q * ld;   // wave-uniform
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int p = 0; p < P; ++p) st.b[s][p] = base[p * plane_units + (size_t)(2 * s) * ld + lane_unit];
+            for (int q = 0; q < Q; ++q) st.b[s][q] = base[(size_t)(2 * s * Q + q) * ld + lane_unit];
 #pragma unroll
         for (int u = 0; u < SUB; ++u) st.w[u] = bits[ti * kTileRows + (wm * SUB + u) * 32 + l32];
     };
@@ -330,13 +336,21 @@ __global__ __launch_bounds__(kThreads) void k_tiles(const TileItem *__restrict__
                 bf16x8 a[SUB];
 #pragma unroll
                 for (int u = 0; u < SUB; ++u) a[u] = operand(st.w[u], 16 * s + 8 * h);
+                uint4 plane[P];
+                if (P == 1) {
+                    plane[0] = st.b[s][0];
+                } else {
+                    const uint32_t x[8] = {st.b[s][0].x,     st.b[s][0].y,     st.b[s][0].z,     st.b[s][0].w,
+                                           st.b[s][Q - 1].x, st.b[s][Q - 1].y, st.b[s][Q - 1].z, st.b[s][Q - 1].w};
+                    split_column<P>(x, plane);
+                }
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     union {
                         uint4 q;
                         bf16x8 v;
                     } b;
-                    b.q = st.b[s][p];
+                    b.q = plane[p];
 #pragma unroll
                     for (int u = 0; u < SUB; ++u)
                         acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b.v, acc[u], 0, 0, 0);
@@ -542,7 +556,7 @@ int tiles_plan(const std::vector<int64_t> &tile_ptr, TileBuffers &tb, hipStream_
 
 size_t tiles_plane_bytes(int64_t n, int cols, int dtype) {
     const size_t n_ct = (size_t)((n + 31) / 32);
-    return (size_t)(dtype == GCN_BF16 ? 1 : 3) * n_ct * 4 * (size_t)round_up(cols, 32) * 16;
+    return (size_t)(dtype == GCN_BF16 ? 1 : 2) * n_ct * 4 * (size_t)round_up(cols, 32) * 16;
 }
 
 PlaneSink tiles_plane_sink(const SpmmArgs &a) {
