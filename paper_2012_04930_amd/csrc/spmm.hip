@@ -589,9 +589,12 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     // "spmm_tiles_first": the other way round; measured the same on the benchmark partition, where both kernels
     // slow each other down through the bytes they pull from the L2s: 254 us together against 195 + 98 us alone).
     hipStream_t gather_stream = st;
-    // the pass that lays the input out for the tile product runs before the two part: beside the gather it takes
-    // three times as long, at the head of the longer of the two paths
-    if (a.tile_ptr) rc = tiles_planes(a, st);
+    // The pass that lays the input out for the tile product.  float32: before the two parts are forked (beside the
+    // gather it takes three times as long, and the tile product's is the longer of the two paths).  bfloat16: at the
+    // head of the tile product's own path, beside the gather (there the gather's path is the longer one: measured
+    // 0.236 against 0.218 ms for the width-128 aggregation of the benchmark partition).
+    const bool planes_first = a.tile_ptr && !(overlap && a.t_dtype == GCN_BF16);
+    if (planes_first) rc = tiles_planes(a, st);
     if (rc != GCN_OK) {
         timing_close(t_all, st);
         return rc;
@@ -600,10 +603,12 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
         if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");
         if (rc == GCN_OK && tunable("spmm_tiles_first", 0) != 0) {
-            rc = tiles_launch(a, a.tile_sums, a.cols, st);
+            if (!planes_first) rc = tiles_planes(a, st);
+            if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, st);
             gather_stream = a.side;
         } else if (rc == GCN_OK) {
-            rc = tiles_launch(a, a.tile_sums, a.cols, a.side);
+            if (!planes_first) rc = tiles_planes(a, a.side);
+            if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, a.side);
         }
         b.finish_mode = kFinishPlainSum;
         if (a.out_dtype != GCN_F32) {
