@@ -327,10 +327,13 @@ def main() -> int:
                 planes = 1 if dtype == B.GCN_BF16 else 3
                 flops = tile_info["n_tiles"] * planes * 2.0 * 128 * 32 * ((w + 31) // 32 * 32)
                 achieved = flops / (avg * 1e-3) / 1e12
+                traffic = read_traffic(wl.name, "tiles", w) if args.dtype is None else None
                 return {"bound": "mfma", "kernel": "k_tiles: %d dense tiles of 128 x 32, %d bfloat16 plane(s), "
                         "width %d" % (tile_info["n_tiles"], planes, w),
                         "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                        "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+                        "traffic": (traffic["fetch_bytes"] + traffic["write_bytes"]) if traffic else None,
+                        "traffic_detail": traffic,
                         "flops_per_launch": flops, "avg_launch_ms": avg,
                         "frac_of_measured_mfma_ceiling": round(achieved / ceil["mfma_bf16_32x32x16_TFLOPs"], 4)}
             if kind.startswith("gemm"):
