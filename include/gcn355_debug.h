@@ -58,7 +58,7 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  *   "spmm_tiles"        -1 / 0 / 1   dense tiles: when they hold a quarter of the entries (default) / never / whenever
  *                                    there is one; read by gcn_graph_create, 0 also per call
  *   "tile_min_entries"  64..4096     entries that make a 128 x 32 tile dense (default 64); read by gcn_graph_create
- *   "tile_chunk"        0 / >= 8     tiles per run when a row block's tiles are cut: half of the average per
+ *   "tile_chunk"        0 / >= 8     tiles per run when a row block's tiles are cut: three quarters of the average per
  *                                    workgroup place (default) / that many; read by gcn_graph_create
  *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
  *   "spmm_tiles_first"  0 / 1        which of the two goes to the graph's own stream: the tile product (default) /
