@@ -56,7 +56,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
     // nn/nt: As[m][k] (k contiguous, padded);  tn: As[k][m] (m contiguous)
     constexpr int kAsFloats = (MODE == kTN) ? BK * BM : BM * (BK + kApad);
     __shared__ __attribute__((aligned(16))) float As[kAsFloats];
-    __shared__ __attribute__((aligned(16))) float Bs[BK * BN];
+    // nn/tn: Bs[k][n] as loaded;  nt: the operand arrives [n][k] and is turned round on the way in, four 4-byte
+    // stores per float4: rows padded by 4 floats so that the four k-quarters of a column land in different banks
+    // (unpadded they hit one bank: 54 % of the kernel's LDS cycles were conflicts)
+    constexpr int BNP = (MODE == kNT) ? BN + 4 : BN;
+    __shared__ __attribute__((aligned(16))) float Bs[BK * BNP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
@@ -151,10 +155,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
             if (idx < B_VECS) {
                 if (MODE == kNT) {
                     const int nn = idx / (BK / 4), kq = idx % (BK / 4);
-                    Bs[(kq * 4 + 0) * BN + nn] = rb[i].x;
-                    Bs[(kq * 4 + 1) * BN + nn] = rb[i].y;
-                    Bs[(kq * 4 + 2) * BN + nn] = rb[i].z;
-                    Bs[(kq * 4 + 3) * BN + nn] = rb[i].w;
+                    Bs[(kq * 4 + 0) * BNP + nn] = rb[i].x;
+                    Bs[(kq * 4 + 1) * BNP + nn] = rb[i].y;
+                    Bs[(kq * 4 + 2) * BNP + nn] = rb[i].z;
+                    Bs[(kq * 4 + 3) * BNP + nn] = rb[i].w;
                 } else {
                     *reinterpret_cast<float4 *>(&Bs[idx * 4]) = rb[i];               // [k][n], same order as idx
                 }
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
             const int cb = (wn * TN + t) * 32 + l32;
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                const float bf = Bs[(h * 8 + s) * BN + cb];
+                const float bf = Bs[(h * 8 + s) * BNP + cb];
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s], bf, acc[t], 0, 0, 0);
             }
         }
