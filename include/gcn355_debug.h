@@ -65,6 +65,8 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  *                                    the gather
  *   "fused_planes"      1 / 0        float32 models: the dense product that writes an aggregation's input also writes the
  *                                    tile product's operand planes (default) / a separate pass does
+ *   "tn_beside"         1 / 0        backward pass: a layer's weight gradient on the graph's own stream beside the input
+ *                                    gradient of the layer below, when an aggregation follows (default) / in line
  *   "spmm_masked"       1 / 0        masked pattern for the last layer's backward aggregation when the train mask
  *                                    holds at most 4/5 of the vertices (default) / never; read by gcn_graph_create
  *   "spmm_phased"       -1 / 0 / 1   phased gather schedule: automatic (default) / never / whenever the shape allows

@@ -562,6 +562,7 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
             HIP_OR_FAIL(hipStreamCreateWithFlags(&g->side, hipStreamNonBlocking));   // default priority
             HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_fork, hipEventDisableTiming));
             HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_join, hipEventDisableTiming));
+            HIP_OR_FAIL(hipEventCreateWithFlags(&g->ev_aux, hipEventDisableTiming));
         }
     }
     // The last layer's backward aggregation reads dLoss/dlogits, whose rows outside the train mask are zero: a
@@ -1147,11 +1148,16 @@ int gcn_backward(gcn_model *m, void *stream) {
     const float keep_scale = m->trained_forward ? (float)(1.0 / (1.0 - (double)m->p)) : 1.0f;
     const bool bf = m->dtype == GCN_BF16;
     bool planes_ready = false;   // the product that wrote this layer's dZ also left it as the tile product's planes
+    bool aux_pending = false;    // a weight gradient is running on the graph's stream
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
         if (l == 1 && m->l1_cached) {
             // dW_1 = P^T dZ_1  (dzs of layer 1 was written without D^-1/2)
             int rc;
+            if (aux_pending) {
+                GCN_HIP(hipStreamWaitEvent(st, g->ev_aux, 0));
+                aux_pending = false;
+            }
             const int t_tn = timing_open(kTimeGemmTN, ly.d_out, st);
             if (bf) {
                 int splits = 0;
@@ -1175,21 +1181,42 @@ int gcn_backward(gcn_model *m, void *stream) {
         planes_ready = false;
         int rc = spmm_launch(a, st);
         if (rc) return rc;
-        // dW_l = H_{l-1}^T G
+        // dW_l = H_{l-1}^T G.  Nothing in the rest of the pass needs it, so above layer 1 it runs on the graph's own
+        // stream beside the input gradient of the layer below (knob "tn_beside"); the pass waits for it before the
+        // next weight gradient (same buffer of partial matrices) and at its end.
         const void *h_prev = l > 1 ? m->layers[l - 2].h : g->x;
-        const int t_tn = timing_open(kTimeGemmTN, ly.d_out, st);
+        if (aux_pending) {
+            GCN_HIP(hipStreamWaitEvent(st, g->ev_aux, 0));
+            aux_pending = false;
+        }
+        // (only when an aggregation follows below: with layer 1 from the cached A_hat X the pass would just wait for
+        // it one product later; measured there 0.563 against 0.554 ms per epoch, here 1.099 against 1.112 ms)
+        const bool beside = l > 1 && !(l == 2 && m->l1_cached) && g->side && g->ev_aux && tunable("tn_beside", 1) != 0;
+        hipStream_t tn_st = st;
+        if (beside) {
+            GCN_HIP(hipEventRecord(g->ev_fork, st));
+            GCN_HIP(hipStreamWaitEvent(g->side, g->ev_fork, 0));
+            tn_st = g->side;
+        }
+        const int t_tn = timing_open(kTimeGemmTN, ly.d_out, tn_st);
         if (bf) {
             int splits = 0;
             rc = gemm_bf16_tn_partials(h_prev, ly.ld_in, ly.g, ly.ld_out, ly.ld_out, g->n, ly.ld_in, ly.ld_out,
-                                       m->partials, m->partial_floats, &splits, st);
-            if (rc) return rc;
-            rc = reduce_partials(m->partials, splits, (size_t)ly.ld_in * ly.ld_out, ly.dw, st);
+                                       m->partials, m->partial_floats, &splits, tn_st);
+            if (!rc) rc = reduce_partials(m->partials, splits, (size_t)ly.ld_in * ly.ld_out, ly.dw, tn_st);
         } else {
             rc = gemm_tn((const float *)h_prev, ly.ld_in, (const float *)ly.g, ly.ld_out, ly.dw, ly.ld_out, g->n,
-                         ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
+                         ly.ld_in, ly.ld_out, m->partials, m->partial_floats, tn_st);
         }
-        timing_close(t_tn, st);
-        if (rc) return rc;
+        timing_close(t_tn, tn_st);
+        if (beside) {   // also after an error: the caller's stream must not run ahead of work already on the other one
+            GCN_HIP(hipEventRecord(g->ev_aux, g->side));
+            aux_pending = true;
+        }
+        if (rc) {
+            if (aux_pending) GCN_HIP(hipStreamWaitEvent(st, g->ev_aux, 0));
+            return rc;
+        }
         if (l > 1) {
             // D^-1/2 dZ_{l-1} = D^-1/2 ((G W_l^T) * [H_{l-1} > 0] * keep_scale)
             Layer &lp = m->layers[l - 2];
@@ -1208,9 +1235,13 @@ int gcn_backward(gcn_model *m, void *stream) {
                     : gemm_nt((const float *)ly.g, ly.ld_out, ly.w, ly.ld_out, (float *)lp.dzs, lp.ld_out, g->n,
                               ly.ld_out, lp.ld_out, next_scale, (const float *)lp.h, lp.ld_out, keep_scale, st, &sink);
             timing_close(t_nt, st);
-            if (rc) return rc;
+            if (rc) {
+                if (aux_pending) GCN_HIP(hipStreamWaitEvent(st, g->ev_aux, 0));
+                return rc;
+            }
         }
     }
+    if (aux_pending) GCN_HIP(hipStreamWaitEvent(st, g->ev_aux, 0));
     m->have_backward = true;
     return GCN_OK;
 }

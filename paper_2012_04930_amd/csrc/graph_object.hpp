@@ -25,10 +25,12 @@ struct gcn_graph {
     gcn::PrepBuffers bwd{};
     int64_t bwd_nnz = 0;
     bool use_bwd = false;
-    // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's
+    // the tile product of an aggregation runs on this stream, beside the gather kernel on the caller's; in the
+    // backward pass also a layer's weight gradient, beside the input gradient of the layer below (ev_aux: its end)
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_aux = nullptr;
     ~gcn_graph() {
+        if (ev_aux) (void)hipEventDestroy(ev_aux);
         if (ev_fork) (void)hipEventDestroy(ev_fork);
         if (ev_join) (void)hipEventDestroy(ev_join);
         if (side) (void)hipStreamDestroy(side);
