@@ -119,6 +119,7 @@ struct gcn_model {
     float *result = nullptr;        // [0] loss [1] accuracy
     long long *result_correct = nullptr;
     bool have_forward = false, have_loss = false, have_backward = false, trained_forward = false;
+    bool dz_units_ready = false;   // gcn_loss_acc left dLoss/dlogits in the tile product's order as well
     // Layer 1 in aggregate-first form: P = A_hat X is computed once (X never changes), then
     // Z_1 = P W_1 and dW_1 = P^T dZ_1 need no aggregation at all.
     bool l1_cached = false;
@@ -1097,6 +1098,7 @@ int gcn_forward(gcn_model *m, int training, void *stream) {
     m->have_forward = true;
     m->trained_forward = training && m->p > 0.0f;
     m->have_loss = m->have_backward = false;
+    m->dz_units_ready = false;   // (the aggregations above reused the buffer)
     return GCN_OK;
 }
 
@@ -1108,12 +1110,20 @@ int gcn_loss_acc(gcn_model *m, float *loss, float *acc, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const gcn_graph *g = m->g;
     Layer &ly = m->layers[m->L - 1];
+    // dLoss/dlogits is the input of the backward pass's first aggregation: the loss kernel writes it in the tile
+    // product's order too, when that aggregation runs one (same arguments as in gcn_backward)
+    const SpmmArgs next = spmm_args(g, ly.dzs, m->dtype, ly.ld_out, ly.g, m->dtype, ly.ld_out, ly.ld_out, ly.d_out,
+                                    kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums, true);
+    PlaneSink sink = tiles_plane_sink(next);
+    if (!loss_can_sink(ly.d_out, m->dtype)) sink.planes = nullptr;
     const int t_loss = timing_open(kTimeLoss, ly.d_out, st);
     int rc = loss_forward(g->n, ly.d_out, (const float *)ly.h, ly.ld_out, g->labels, g->mask, g->pb.dinv, g->n_train,
-                          ly.dzs, m->dtype, ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st);
+                          ly.dzs, m->dtype, ly.ld_out, m->loss_part, m->corr_part, m->result, m->result_correct, st,
+                          &sink);
     timing_close(t_loss, st);
     if (rc) return rc;
     m->have_loss = true;
+    m->dz_units_ready = sink.planes != nullptr;
     if (loss || acc) {
         float host[2];
         GCN_HIP(hipMemcpyAsync(host, m->result, sizeof(host), hipMemcpyDeviceToHost, st));
@@ -1147,7 +1157,10 @@ int gcn_backward(gcn_model *m, void *stream) {
     const gcn_graph *g = m->g;
     const float keep_scale = m->trained_forward ? (float)(1.0 / (1.0 - (double)m->p)) : 1.0f;
     const bool bf = m->dtype == GCN_BF16;
-    bool planes_ready = false;   // the product that wrote this layer's dZ also left it as the tile product's planes
+    // the kernel that wrote this layer's dZ also left it in the tile product's order (the loss kernel for the last
+    // layer, the input-gradient product for the others); good for one pass: later aggregations reuse the buffer
+    bool planes_ready = m->dz_units_ready;
+    m->dz_units_ready = false;
     bool aux_pending = false;    // a weight gradient is running on the graph's stream
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];

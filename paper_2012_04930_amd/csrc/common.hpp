@@ -187,7 +187,9 @@ constexpr int kLossBlocks = 4096;
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
                  const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
                  long long *corr_part, float *result /* [0] loss, [1] accuracy, as float */,
-                 long long *result_correct, hipStream_t st);
+                 long long *result_correct, hipStream_t st, const struct PlaneSink *sink = nullptr);
+// whether loss_forward writes dLoss/dlogits through a sink for this shape (at most 64 classes, float32)
+bool loss_can_sink(int classes, int dz_dtype);
 // w_l -= lr dw_l for every layer l in one launch; end[l] = number of elements of layers 0..l together
 constexpr int kMaxLayers = 16;
 struct SgdLayers {

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void k_loss_small(int64_t n, int classes,
                                                          const float *__restrict__ dinv, float inv_ntrain,
                                                          TDz *__restrict__ dzs, int ld_dz,
                                                          double *__restrict__ loss_part,
-                                                         long long *__restrict__ corr_part) {
+                                                         long long *__restrict__ corr_part, PlaneSink sink) {
     constexpr int kLanes = 16, kPerLane = 4;
     __shared__ double s_loss[kThreads / 64];
     __shared__ long long s_corr[kThreads / 64];
@@ -146,15 +146,28 @@ __global__ __launch_bounds__(kThreads) void k_loss_small(int64_t n, int classes,
     const int64_t groups_total = (int64_t)gridDim.x * (kThreads / kLanes);
     double my_loss = 0.0;
     long long my_corr = 0;
-    for (int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * (64 / kLanes) + grp; v < n; v += groups_total) {
-        const float *z = logits + v * ld;
-        TDz *g = dzs + v * ld_dz;
-        if (!mask[v]) {
+    // With a sink the gradient also goes out in the order the tile product of the backward aggregation reads it
+    // (tiles.hip: rows 32 ct + 8 kg + 4 half + 0..3 of column c are the 16 bytes at units[((ct * 4 + kg) * 2 + half) *
+    // ld + c]).  The four vertices of a wave are four consecutive rows (the group count is a multiple of four), so
+    // lane (group, sub) writes element `group` of the unit of column sub + 16 i: a wave's store is 256 contiguous
+    // bytes.  Rows from n up to the last whole block of 32 are written as zero.
+    float *units = static_cast<float *>(sink.planes);
+    const int64_t v_end = units ? (int64_t)sink.n_ct * 32 : n;
+    auto to_units = [&](int64_t v, int c, float x) {
+        if (units && c < sink.ld)
+            units[((((v >> 5) * 4 + ((v >> 3) & 3)) * 2 + ((v >> 2) & 1)) * sink.ld + c) * 4 + (v & 3)] = x;
+    };
+    for (int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * (64 / kLanes) + grp; v < v_end; v += groups_total) {
+        if (v >= n || !mask[v]) {
 #pragma unroll
-            for (int i = 0; i < kPerLane; ++i)
-                if (sub + kLanes * i < classes) g[sub + kLanes * i] = narrow<TDz>(0.0f);
+            for (int i = 0; i < kPerLane; ++i) {
+                if (v < n && sub + kLanes * i < classes) dzs[v * ld_dz + sub + kLanes * i] = narrow<TDz>(0.0f);
+                to_units(v, sub + kLanes * i, 0.0f);
+            }
             continue;
         }
+        const float *z = logits + v * ld;
+        TDz *g = dzs + v * ld_dz;
         float x[kPerLane];
         float m = -INFINITY;
         int arg = 0x7fffffff;
@@ -188,7 +201,13 @@ __global__ __launch_bounds__(kThreads) void k_loss_small(int64_t n, int classes,
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
             const int c = sub + kLanes * i;
-            if (c < classes) g[c] = narrow<TDz>((expf(x[i] - lse) - (c == y ? 1.0f : 0.0f)) * scale);
+            float gv = 0.0f;
+            if (c < classes) {
+                const TDz stored = narrow<TDz>((expf(x[i] - lse) - (c == y ? 1.0f : 0.0f)) * scale);
+                g[c] = stored;
+                gv = widen(stored);
+            }
+            to_units(v, c, gv);
         }
         if (sub == 0) {
             my_loss += (double)(lse - z[y]);
@@ -370,19 +389,25 @@ int fill_zero(void *p, size_t bytes, hipStream_t st) {
     return GCN_OK;
 }
 
+bool loss_can_sink(int classes, int dz_dtype) { return classes <= 64 && dz_dtype == GCN_F32; }
+
 int loss_forward(int64_t n, int classes, const float *logits, int ld, const int32_t *labels, const uint8_t *mask,
                  const float *dinv, int64_t n_train, void *dzs, int dz_dtype, int ld_dz, double *loss_part,
-                 long long *corr_part, float *result, long long *result_correct, hipStream_t st) {
-    int blocks = (int)(classes <= 64 ? (n + 15) / 16 : (n + 3) / 4);
+                 long long *corr_part, float *result, long long *result_correct, hipStream_t st,
+                 const PlaneSink *sink) {
+    const PlaneSink none{nullptr, 0, 0};
+    const bool sinks = sink && sink->planes && loss_can_sink(classes, dz_dtype);
+    int blocks = (int)(classes <= 64 ? (n + 15) / 16 + 2 : (n + 3) / 4);   // (+ 2: the rows up to a whole block of 32)
     if (blocks > kLossBlocks) blocks = kLossBlocks;
     if (blocks < 1) blocks = 1;
     const float inv = (float)(1.0 / (double)n_train);
     if (classes <= 64 && dz_dtype == GCN_BF16)
         k_loss_small<bf16_t><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
-                                                                      (bf16_t *)dzs, ld_dz, loss_part, corr_part);
+                                                                      (bf16_t *)dzs, ld_dz, loss_part, corr_part, none);
     else if (classes <= 64)
         k_loss_small<float><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
-                                                                     (float *)dzs, ld_dz, loss_part, corr_part);
+                                                                     (float *)dzs, ld_dz, loss_part, corr_part,
+                                                                     sinks ? *sink : none);
     else if (dz_dtype == GCN_BF16)
         k_loss<bf16_t><<<dim3(blocks), dim3(kThreads), 0, st>>>(n, classes, logits, ld, labels, mask, dinv, inv,
                                                                 (bf16_t *)dzs, ld_dz, loss_part, corr_part);
