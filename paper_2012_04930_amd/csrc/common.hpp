@@ -253,7 +253,7 @@ struct SpmmArgs {
     const void *tile_folds;   // row blocks whose runs are added up afterwards
     int32_t n_folds, n_slots;
     float *tile_partial;      // n_slots x kTileRows x cols floats
-    void *tile_planes;        // tiles_plane_bytes(n, cols, t_dtype): the input split and reordered for the matrix cores
+    void *tile_planes;        // tiles_plane_bytes(n, cols, t_dtype): the input in the order the tile product reads it
     // Overlap of the two parts (all four set, or none): the tile product runs on `side` into tile_sums [n x cols
     // floats] while the gather kernel writes plain sums to out on the caller's stream; a third launch adds the two
     // and finishes the rows.  Without them the gather kernel follows the tile product and finishes the rows itself.
@@ -264,8 +264,8 @@ struct SpmmArgs {
     int finish_mode;     // set by spmm_launch, see SpmmFinish
     int planes_ready;    // tile_planes already holds this input (its producer wrote it through a PlaneSink)
 };
-// Where the producer of an aggregation's float32 input also leaves it as the tile product's operand planes
-// (planes == nullptr: nowhere); n_ct blocks of 32 rows, `ld` 16-byte units per block and k-octet.
+// Where the producer of an aggregation's float32 input also leaves it in the order the tile product reads it
+// (planes == nullptr: nowhere); n_ct blocks of 32 rows, per block and k-octet `ld` units of two 16-byte halves.
 struct PlaneSink {
     void *planes;
     int n_ct;
@@ -281,7 +281,7 @@ enum SpmmFinish {
     kFinishPlainSum = 2    // store the plain sum (float32 output); a later launch finishes the rows
 };
 size_t tiles_plane_bytes(int64_t n, int cols, int dtype);
-// the aggregation's input as the tile product's operand planes, unless its producer has written them
+// the aggregation's input in the order the tile product reads it, unless its producer has written that
 int tiles_planes(const SpmmArgs &a, hipStream_t st);
 // dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling); after tiles_planes
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st);

@@ -19,9 +19,12 @@
 // (8 + 8 + 8 significant bits: hi = x with the low 16 bits of its encoding cleared, mid likewise from x - hi, lo
 // = the rest, which then has at most 8 significant bits; all three subtractions are exact).  Ones and zeros are
 // exact in bfloat16 too, so three passes of v_mfma_f32_32x32x16_bf16 over the same accumulator add exactly
-// the terms the float32 gather adds, in float32, in another order.  The split is done once per aggregation by a
-// pass over the input (k_tile_planes), which also lays the values out in the order the instruction reads them.  (Values below 2^-110 lose their last bits:
+// the terms the float32 gather adds, in float32, in another order.  (Values below 2^-110 lose their last bits:
 // bfloat16 has float32's exponent range but lo is 2^-16 times smaller.)  bfloat16 input rows need one pass.
+// The input reaches k_tiles in the order the instruction reads its second operand ("units", see k_tile_planes);
+// float32 units are split into the three planes in registers.  Who writes the units: the kernel that produces the
+// aggregation's input, from its epilogue (plane_sink.hpp; the dense products and the loss kernel), or else the
+// pass k_tile_planes.
 #include <algorithm>
 #include <vector>
 
