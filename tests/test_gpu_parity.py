@@ -426,8 +426,9 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
     """Layer 1's feature transform from packed three-plane operands ("gemm_split") against the float32 matrix
     instruction: both within the bar of the oracle, and within 1e-5 of each other.  The operand planes that the
     dense products write for the tile product ("fused_planes") are bit for bit what the separate pass writes, so
-    every tensor of the epoch is identical with and without.  A partition with dense tiles, 602 input columns
-    (19 k-blocks, the last one padded), dropout on."""
+    every tensor of the epoch is identical with and without; so it is with the upper layer's weight gradient beside
+    the input gradient ("tn_beside") or in line.  A partition with dense tiles, 602 input columns (19 k-blocks, the
+    last one padded), dropout on."""
     wl = workloads.reddit_partition(scale=0.12)
     g = H.gpu_graph(B, wl)
     assert B.gcn_graph_tile_info(g)["in_use"]
@@ -437,9 +438,17 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
             B.gcn_set_tunable("gemm_split", split)
             B.gcn_set_tunable("fused_planes", fused)
             _, runs[(split, fused)] = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
+        B.gcn_set_tunable("gemm_split", 1)
+        B.gcn_set_tunable("fused_planes", 1)
+        B.gcn_set_tunable("tn_beside", 0)       # the upper layer's weight gradient in line instead of beside
+        _, in_line = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
     finally:
         B.gcn_set_tunable("gemm_split", 1)
         B.gcn_set_tunable("fused_planes", 1)
+        B.gcn_set_tunable("tn_beside", 1)
+    for name in ("H", "dW", "W", "dZ"):
+        for x, y in zip(runs[(1, 1)][name], in_line[name]):
+            np.testing.assert_array_equal(x, y)
     for key, gpu in runs.items():
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=0.25, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
