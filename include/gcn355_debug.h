@@ -52,6 +52,10 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  *   "gemm_split"        1 / 0        float32 models: layer 1's feature transform on the bfloat16 matrix instruction
  *                                    from three-plane operands (default) / on the float32 instruction; read by
  *                                    gcn_model_workspace_bytes and gcn_model_create
+ *   "gemm_split_tn"     1 / 0        with "gemm_split" and layer 1 from the cached A_hat X: its weight gradient the
+ *                                    same way, the vertices (the shared index) cut over workgroups (default) / on
+ *                                    the float32 instruction; read by gcn_model_workspace_bytes and gcn_model_create
+ *   "split_tn_wgs"      >= 1         workgroups that product aims at when it cuts the shared index (default 256)
  *   "tile_slots"        >= 256       workgroups of the tile product the chip is taken to hold at a time when its
  *                                    work items are planned (default 768); read by gcn_graph_create
  *   "tile_run_min"      >= 8         a row block with up to 1.5 x this many tiles is never cut (default 16)

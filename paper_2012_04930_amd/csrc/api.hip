@@ -130,6 +130,8 @@ struct gcn_model {
     bool l1_split = false;
     void *sp_a = nullptr;    // packed left operand [n x ld_in]
     void *sp_wt = nullptr;   // packed right operand [ld_out x ld_in]
+    void *sp_at = nullptr;   // the same matrix as sp_a transposed, packed left [ld_in x n] (weight gradient)
+    void *sp_gu = nullptr;   // the weight gradient's right operand [n x ld_out] in the tile product's order
 };
 
 namespace {
@@ -334,6 +336,17 @@ void carve_model(Carver &c, gcn_model &m) {
         const Layer &l1 = m.layers[0];
         m.sp_a = c.take<char>(packed_bytes(n, l1.ld_in, true));
         m.sp_wt = c.take<char>(packed_bytes(l1.ld_out, l1.ld_in, false));
+        // The weight gradient the same way only when layer 1 works from the cached A_hat X ("gemm_split_tn", default
+        // 1): there dZ_1 comes out of the product above it already in the order the right operand is read in, and an
+        // epoch gains 4 % (1,946 against 1,875 epochs/s on the Reddit-shaped partition).  Behind an aggregation the
+        // product itself is as much faster (83 against 91 us), but the epoch is not (938 against 944 epochs/s; the
+        // clock the chip settles to under the loop drops with every product moved to the bfloat16 instruction).
+        if (m.l1_cached && tunable("gemm_split_tn", 1) != 0) {
+            m.sp_at = c.take<char>(packed_bytes(l1.ld_in, n, true));
+            m.sp_gu = c.take<char>(tiles_plane_bytes(n, l1.ld_out, GCN_F32));
+            const size_t need = gemm_split_tn_partial_floats(l1.ld_in, n, l1.ld_out);
+            if (need > pf) pf = need;
+        }
     }
     int widest = 0;   // columns of the widest single aggregation launch
     for (auto &ly : m.layers) widest = ly.ld_out > widest ? ly.ld_out : widest;
@@ -931,6 +944,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     if (!rc && m->l1_split) {
         const float *src = (const float *)(m->l1_cached ? m->pax : g->x);
         rc = pack_rows(src, g->ldf, g->n, g->ldf, m->sp_a, true, st);
+        if (!rc && m->sp_at) rc = pack_transposed(src, g->ldf, g->n, g->ldf, m->sp_at, true, st);
     }
     if (rc) {
         delete m;
@@ -1034,6 +1048,16 @@ int l1_split_forward(gcn_model *m, float *c, const float *rowscale, const Activa
     int rc = pack_transposed(ly.w, ly.ld_out, ly.ld_in, ly.ld_out, m->sp_wt, false, st);
     if (rc) return rc;
     return gemm_split(m->sp_a, m->sp_wt, c, ly.ld_out, m->g->n, ly.ld_in, ly.ld_out, rowscale, act, st, sink);
+}
+
+// dW_1 = P^T dZ_1 the same way: `rows` = dZ_1 [n x ld_out] is put in the order the product's right operand is read
+// in unless its producer left it in m->sp_gu that way; the left operand P^T was packed when the model was made
+int l1_split_backward(gcn_model *m, const float *rows, bool have_units, hipStream_t st) {
+    const Layer &ly = m->layers[0];
+    int rc = have_units ? GCN_OK : units_from_rows(rows, ly.ld_out, m->g->n, ly.ld_out, m->sp_gu, st);
+    if (rc) return rc;
+    return gemm_split_tn(m->sp_at, m->sp_gu, (int)round_up(ly.ld_out, 32), ly.dw, ly.ld_out, ly.ld_in, m->g->n,
+                         ly.ld_out, m->partials, m->partial_floats, st);
 }
 
 }  // namespace
@@ -1162,6 +1186,8 @@ int gcn_backward(gcn_model *m, void *stream) {
     bool planes_ready = m->dz_units_ready;
     m->dz_units_ready = false;
     bool aux_pending = false;    // a weight gradient is running on the graph's stream
+    const bool split_tn = m->sp_at != nullptr;   // dW_1 = P^T dZ_1 on the bfloat16 instruction
+    bool gu_ready = false;       // its right operand is in m->sp_gu
     for (int l = m->L; l >= 1; --l) {
         Layer &ly = m->layers[l - 1];
         if (l == 1 && m->l1_cached) {
@@ -1178,6 +1204,8 @@ int gcn_backward(gcn_model *m, void *stream) {
                                            m->partials, m->partial_floats, &splits, st);
                 if (rc) return rc;
                 rc = reduce_partials(m->partials, splits, (size_t)ly.ld_in * ly.ld_out, ly.dw, st);
+            } else if (split_tn) {
+                rc = l1_split_backward(m, (const float *)ly.dzs, gu_ready, st);
             } else {
                 rc = gemm_tn((const float *)m->pax, g->ldf, (const float *)ly.dzs, ly.ld_out, ly.dw, ly.ld_out, g->n,
                              ly.ld_in, ly.ld_out, m->partials, m->partial_floats, st);
@@ -1241,6 +1269,9 @@ int gcn_backward(gcn_model *m, void *stream) {
                                                 lp.d_out, kEpiNone, m->tile_sums, m->chunk_sums, m->gather_sums, false);
                 sink = tiles_plane_sink(next);
                 planes_ready = sink.planes != nullptr;
+            } else if (split_tn && tunable("fused_planes", 1) != 0) {   // dZ_1 goes straight into the weight gradient
+                sink = PlaneSink{m->sp_gu, (int)((g->n + 31) / 32), (int)round_up(lp.ld_out, 32)};
+                gu_ready = true;
             }
             const int t_nt = timing_open(kTimeGemmNT, lp.d_out, st);
             rc = bf ? gemm_bf16_nt(ly.g, ly.ld_out, ly.wb, ly.ld_out, lp.dzs, lp.ld_out, g->n, ly.ld_out, lp.ld_out,

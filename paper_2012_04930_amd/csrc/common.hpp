@@ -283,6 +283,8 @@ enum SpmmFinish {
 size_t tiles_plane_bytes(int64_t n, int cols, int dtype);
 // the aggregation's input in the order the tile product reads it, unless its producer has written that
 int tiles_planes(const SpmmArgs &a, hipStream_t st);
+// a float32 matrix t [n x cols] (cols even) in that order: units of tiles_plane_bytes(n, cols, GCN_F32) bytes
+int units_from_rows(const float *t, int ld_t, int64_t n, int cols, void *units, hipStream_t st);
 // dst [n x ld_dst] = the sums over the dense tiles only (float32, no scaling); after tiles_planes
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st);
 int spmm_launch(const SpmmArgs &a, hipStream_t st);
@@ -333,6 +335,12 @@ int pack_transposed(const float *src, int ld, int64_t rows, int cols, void *dst,
 // c [M x N] = act(rowscale * (a b^T)), a [M x K] packed left, b [N x K] packed right
 int gemm_split(const void *a, const void *b, float *c, int ldc, int64_t M, int64_t K, int N, const float *rowscale,
                const Activation *act /* may be null */, hipStream_t st, const PlaneSink *sink = nullptr);
+// c [M x N] = a b, a [M x K] packed left, b [K x N] as float32 units in the tile product's order (tiles.hip:
+// units_from_rows; b_ld units per octet and half).  K is cut over workgroups; the partial matrices are added in
+// ascending order.  partials holds gemm_split_tn_partial_floats(M, K, N) floats.
+size_t gemm_split_tn_partial_floats(int64_t M, int64_t K, int N);
+int gemm_split_tn(const void *a, const void *b_units, int b_ld, float *c, int ldc, int64_t M, int64_t K, int N,
+                  float *partials, size_t partial_floats, hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
 // Event timing of launches (api.hip): timing_open records an event on the stream the work is about to be launched

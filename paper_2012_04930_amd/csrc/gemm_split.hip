@@ -44,8 +44,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes in fli
 struct SplitArgs {
     const char *a;      // packed float32, a_tiles x nkb chunks
     int64_t a_tiles;
-    const char *b;      // packed planes, b_tiles x nkb chunks
+    const char *b;      // packed planes, b_tiles x nkb chunks; or (UNITS) float32 units in the tile product's order
     int b_tiles;
+    int b_ld;           // UNITS: units per (32-row block, octet, half), a multiple of 32
+    int64_t kb_per_split;   // 0: a workgroup runs over all of K and finishes its outputs; else blockIdx.y takes this
+                            // many k-blocks and writes its own partial matrix (M x ldc, one after the other at c)
     int64_t nkb;        // k-blocks (chunks per row tile)
     float *c;
     int ldc;
@@ -70,7 +73,7 @@ struct SplitArgs {
 constexpr int kThreads = 256;
 constexpr int BM = 128;
 
-template <int TN>
+template <int TN, bool UNITS>
 __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     __shared__ __attribute__((aligned(16))) char Bs[2][TN * kChunkBytes];
 
@@ -81,7 +84,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     const int ntiles = (g.b_tiles + TN - 1) / TN;
     const int64_t mt0 = (int64_t)(blockIdx.x / ntiles) * (BM / 32) + wave;   // this wave's row tile
     const int nt0 = (blockIdx.x % ntiles) * TN;
-    const int64_t kb_beg = 0, kb_end = g.nkb;
+    int64_t kb_beg = 0, kb_end = g.nkb;
+    if (g.kb_per_split > 0) {
+        kb_beg = (int64_t)blockIdx.y * g.kb_per_split;
+        kb_end = kb_beg + g.kb_per_split < g.nkb ? kb_beg + g.kb_per_split : g.nkb;
+    }
 
     f32x16 acc[TN];
 #pragma unroll
@@ -92,8 +99,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     struct AFrags {
         u32x4 f[BK / 16][2];   // eight float32 encodings per step
     };
-    constexpr int B_VECS = TN * kChunkVecs;   // 16-byte vectors of the right operand per k-block
+    // Right operand per k-block.  Packed planes: TN chunks = TN x 384 vectors of 16 bytes, copied as they are.
+    // UNITS (the matrix is given in the tile product's order: per block of 32 shared indices, octet kg, half and
+    // column one 16-byte piece of four float32): TN x 4 x 32 (column, octet) pairs, two pieces each, split into the
+    // three planes on the way into LDS, where the pair lands at lane (kg & 1) * 32 + column of step kg >> 1.
+    constexpr int B_VECS = UNITS ? TN * 4 * 32 * 2 : TN * kChunkVecs;
     constexpr int B_PER = (B_VECS + kThreads - 1) / kThreads;
+    static_assert(!UNITS || (B_VECS % (2 * kThreads) == 0), "whole pairs per thread");
     struct BRegs {
         u32x4 v[B_PER];
     };
@@ -102,16 +114,27 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     const int64_t a_tile = mt0 < g.a_tiles ? mt0 : g.a_tiles - 1;
     const char *abase = g.a + a_tile * g.nkb * kLeftChunkBytes;
     const uint32_t oa = (uint32_t)lane * 16u;
-    const char *bbase = g.b + (int64_t)nt0 * g.nkb * kChunkBytes;
+    const char *bbase = UNITS ? g.b : g.b + (int64_t)nt0 * g.nkb * kChunkBytes;
     uint32_t ob[B_PER];
+    int sb[B_PER];   // UNITS: where a pair's plane 0 goes in the LDS buffer
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
-        const int v = (tid + i * kThreads) % B_VECS;   // threads past the end load again what others load
-        const int t = v / kChunkVecs, w = v % kChunkVecs;
-        const int tile = nt0 + t < g.b_tiles ? t : g.b_tiles - 1 - nt0;
-        ob[i] = (uint32_t)((int64_t)tile * g.nkb * kChunkBytes + w * 16);
+        if (UNITS) {
+            const int pair = tid + (i / 2) * kThreads, half = i & 1;
+            const int c32 = pair % 32, kg = (pair / 32) % 4, t = pair / 128;
+            const int col = (nt0 + t < g.b_tiles ? nt0 + t : g.b_tiles - 1) * 32 + c32;
+            ob[i] = (uint32_t)(((kg * 2 + half) * g.b_ld + col) * 16);
+            sb[i] = t * kChunkBytes + ((kg >> 1) * 64 + (kg & 1) * 32 + c32) * 16;
+        } else {
+            const int v = (tid + i * kThreads) % B_VECS;   // threads past the end load again what others load
+            const int t = v / kChunkVecs, w = v % kChunkVecs;
+            const int tile = nt0 + t < g.b_tiles ? t : g.b_tiles - 1 - nt0;
+            ob[i] = (uint32_t)((int64_t)tile * g.nkb * kChunkBytes + w * 16);
+            sb[i] = 0;
+        }
     }
     const int64_t kb_last = kb_end - 1;
+    const int64_t b_block = UNITS ? (int64_t)8 * g.b_ld * 16 : kChunkBytes;   // bytes of the right operand per k-block
 
     auto load_a = [&](AFrags &fr, int64_t kb) {
         kb = kb < kb_last ? kb : kb_last;
@@ -124,15 +147,28 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     };
     auto load_b = [&](BRegs &rb, int64_t kb) {
         kb = kb < kb_last ? kb : kb_last;
-        const char *base = bbase + kb * kChunkBytes;
+        const char *base = bbase + kb * b_block;
 #pragma unroll
         for (int i = 0; i < B_PER; ++i) rb.v[i] = *reinterpret_cast<const u32x4 *>(base + ob[i]);
     };
     auto stash_b = [&](const BRegs &rb, const int buf) {
+        if (UNITS) {
 #pragma unroll
-        for (int i = 0; i < B_PER; ++i)
-            if (B_VECS % kThreads == 0 || tid + i * kThreads < B_VECS)
-                *reinterpret_cast<u32x4 *>(&Bs[buf][(tid + i * kThreads) * 16]) = rb.v[i];
+            for (int i = 0; i + 1 < B_PER; i += 2) {
+                const uint32_t x[8] = {rb.v[i][0],     rb.v[i][1],     rb.v[i][2],     rb.v[i][3],
+                                       rb.v[i + 1][0], rb.v[i + 1][1], rb.v[i + 1][2], rb.v[i + 1][3]};
+                uint4 o[kPlanes];
+                split_column<kPlanes>(x, o);
+#pragma unroll
+                for (int p = 0; p < kPlanes; ++p)
+                    *reinterpret_cast<uint4 *>(&Bs[buf][sb[i] + p * (BK / 16) * 1024]) = o[p];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i)
+                if (B_VECS % kThreads == 0 || tid + i * kThreads < B_VECS)
+                    *reinterpret_cast<u32x4 *>(&Bs[buf][(tid + i * kThreads) * 16]) = rb.v[i];
+        }
     };
     auto right = [&](const int buf, const int t, const int ks, const int p) {
         return *reinterpret_cast<const bf16x8 *>(&Bs[buf][t * kChunkBytes + (p * (BK / 16) + ks) * 1024 + lane * 16]);
@@ -192,7 +228,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
     };
     static_assert(kPlanes == 3 && (TN == 1 || TN % 2 == 0), "the products above are written out for three planes");
 
-    {
+    if (kb_beg < kb_end) {   // (a split past the end of K has nothing to add and writes zeros)
         // Loads run two k-blocks ahead of their use: three register sets for each operand, taken in turn.  (A set
         // is never copied: a copy would have to wait for the loads into it.)
         AFrags f0, f1, f2;
@@ -226,7 +262,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
         if (kb + 1 < kb_end) step(f1, f0, b2, b0, kb + 1);
     }
 
-    const bool to_sink = g.sink.planes != nullptr;
+    float *cbase = g.c;
+    if (g.kb_per_split > 0) cbase += (int64_t)blockIdx.y * g.M * g.ldc;   // this split's partial matrix
+    const bool to_sink = g.sink.planes != nullptr && g.kb_per_split == 0;
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int col = (nt0 + t) * 32 + l32;
@@ -237,9 +275,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_gemm_split(SplitArgs g) {
             float x = 0.0f;
             if (row < g.M && col < g.ldc) {
                 x = col < g.N ? acc[t][v] : 0.0f;
-                if (g.rowscale) x *= g.rowscale[row];
-                x = activate(x, g.act, row, col);
-                g.c[row * g.ldc + col] = x;
+                if (g.kb_per_split == 0) {
+                    if (g.rowscale) x *= g.rowscale[row];
+                    x = activate(x, g.act, row, col);
+                }
+                cbase[row * g.ldc + col] = x;
             }
             xs[v] = x;
         }
@@ -339,6 +379,17 @@ int pack_transposed(const float *src, int ld, int64_t rows, int cols, void *dst,
     return GCN_OK;
 }
 
+namespace {
+int tn_split_count(int64_t M, int64_t K, int N) {
+    const int bn = N > 64 ? 128 : 64;
+    const int64_t tiles = (M + BM - 1) / BM * ((N + bn - 1) / bn);
+    int64_t splits = tunable("split_tn_wgs", 256) / (tiles > 0 ? tiles : 1);   // one workgroup per compute unit (measured better than two: fewer partial matrices)
+    const int64_t max_by_k = (K + 8 * BK - 1) / (8 * BK);   // at least 256 of the shared index per split
+    if (splits > max_by_k) splits = max_by_k;
+    return splits < 1 ? 1 : (int)splits;
+}
+}  // namespace
+
 int gemm_split(const void *a, const void *b, float *c, int ldc, int64_t M, int64_t K, int N, const float *rowscale,
                const Activation *act, hipStream_t st, const PlaneSink *sink) {
     if (M <= 0) return GCN_OK;
@@ -347,17 +398,47 @@ int gemm_split(const void *a, const void *b, float *c, int ldc, int64_t M, int64
         return GCN_EINVAL;
     }
     const int64_t nkb = (K + BK - 1) / BK;
-    SplitArgs g{(const char *)a, (M + 31) / 32, (const char *)b, (N + 31) / 32, nkb, c, ldc, M, N, rowscale,
+    SplitArgs g{(const char *)a, (M + 31) / 32, (const char *)b, (N + 31) / 32, 0, 0, nkb, c, ldc, M, N, rowscale,
                 act ? *act : Activation{kActNone, 0, 0u, 1.0f, 0ull}, sink ? *sink : PlaneSink{nullptr, 0, 0}};
     const unsigned mtiles = (unsigned)((M + BM - 1) / BM);
     if (N > 64)
-        k_gemm_split<4><<<dim3(mtiles * (unsigned)((N + 127) / 128)), dim3(kThreads), 0, st>>>(g);
+        k_gemm_split<4, false><<<dim3(mtiles * (unsigned)((N + 127) / 128)), dim3(kThreads), 0, st>>>(g);
     else if (N > 32)
-        k_gemm_split<2><<<dim3(mtiles), dim3(kThreads), 0, st>>>(g);
+        k_gemm_split<2, false><<<dim3(mtiles), dim3(kThreads), 0, st>>>(g);
     else
-        k_gemm_split<1><<<dim3(mtiles), dim3(kThreads), 0, st>>>(g);
+        k_gemm_split<1, false><<<dim3(mtiles), dim3(kThreads), 0, st>>>(g);
     GCN_LAUNCH_CHECK();
     return GCN_OK;
+}
+
+size_t gemm_split_tn_partial_floats(int64_t M, int64_t K, int N) {
+    return (size_t)tn_split_count(M, K, N) * (size_t)M * (size_t)padded_width(N);
+}
+
+int gemm_split_tn(const void *a, const void *b_units, int b_ld, float *c, int ldc, int64_t M, int64_t K, int N,
+                  float *partials, size_t partial_floats, hipStream_t st) {
+    if (M <= 0) return GCN_OK;
+    if (K <= 0 || N <= 0 || ldc % 16 != 0 || N > ldc || b_ld % 32 != 0 || b_ld < N) {
+        set_error("gemm_split_tn: bad shape M=%lld K=%lld N=%d ldc=%d units ld=%d", (long long)M, (long long)K, N, ldc,
+                  b_ld);
+        return GCN_EINVAL;
+    }
+    const int64_t nkb = (K + BK - 1) / BK;
+    const int splits = tn_split_count(M, K, N);
+    if (!partials || (size_t)splits * (size_t)M * (size_t)ldc > partial_floats) {
+        set_error("gemm_split_tn: partial buffer too small");
+        return GCN_EWORKSPACE;
+    }
+    SplitArgs g{(const char *)a, (M + 31) / 32, (const char *)b_units, b_ld / 32, b_ld, (nkb + splits - 1) / splits, nkb,
+                partials, ldc, M, N, nullptr, Activation{kActNone, 0, 0u, 1.0f, 0ull}, PlaneSink{nullptr, 0, 0}};
+    const unsigned mtiles = (unsigned)((M + BM - 1) / BM);
+    const unsigned ys = (unsigned)splits;
+    if (N > 64)
+        k_gemm_split<4, true><<<dim3(mtiles * (unsigned)((N + 127) / 128), ys), dim3(kThreads), 0, st>>>(g);
+    else   // (one column tile would leave half the threads without a pair to load: it runs as two, the second clamped)
+        k_gemm_split<2, true><<<dim3(mtiles, ys), dim3(kThreads), 0, st>>>(g);
+    GCN_LAUNCH_CHECK();
+    return reduce_partials(partials, splits, (size_t)M * (size_t)ldc, c, st);
 }
 
 }  // namespace gcn

@@ -591,6 +591,21 @@ int tiles_planes(const SpmmArgs &a, hipStream_t st) {
     return GCN_OK;
 }
 
+int units_from_rows(const float *t, int ld_t, int64_t n, int cols, void *units, hipStream_t st) {
+    if (n <= 0) return GCN_OK;
+    if (cols <= 0 || cols % 2 != 0 || ld_t < cols) {
+        set_error("units_from_rows: an even number of columns within the leading dimension (cols=%d ld=%d)", cols, ld_t);
+        return GCN_EINVAL;
+    }
+    const int n_ct = (int)((n + 31) / 32);
+    const int ld = (int)round_up(cols, 32);
+    const int64_t threads = (int64_t)n_ct * 4 * (ld / 2);
+    k_tile_planes<float><<<dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, st>>>(t, ld_t, n, n_ct, cols, ld,
+                                                                                     static_cast<uint4 *>(units));
+    GCN_LAUNCH_CHECK();
+    return GCN_OK;
+}
+
 // (after tiles_planes, on a stream ordered behind it)
 int tiles_launch(const SpmmArgs &a, float *dst, int ld_dst, hipStream_t st) {
     if (a.cols > 256 || a.n_items < 1 || (a.n_slots > 0 && !a.tile_partial) || !a.tile_planes) {

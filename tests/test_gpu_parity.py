@@ -427,7 +427,8 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
     instruction: both within the bar of the oracle, and within 1e-5 of each other.  The operand planes that the
     dense products write for the tile product ("fused_planes") are bit for bit what the separate pass writes, so
     every tensor of the epoch is identical with and without; so it is with the upper layer's weight gradient beside
-    the input gradient ("tn_beside") or in line.  A partition with dense tiles, 602 input columns (19 k-blocks, the
+    the input gradient ("tn_beside") or in line.  Layer 1's weight gradient the same way ("gemm_split_tn", the shared
+    index being the vertices, cut over workgroups) against the float32 one.  A partition with dense tiles, 602 input columns (19 k-blocks, the
     last one padded), dropout on."""
     wl = workloads.reddit_partition(scale=0.12)
     g = H.gpu_graph(B, wl)
@@ -442,22 +443,29 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
         B.gcn_set_tunable("fused_planes", 1)
         B.gcn_set_tunable("tn_beside", 0)       # the upper layer's weight gradient in line instead of beside
         _, in_line = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
+        B.gcn_set_tunable("tn_beside", 1)
+        B.gcn_set_tunable("gemm_split_tn", 0)   # layer 1's weight gradient on the float32 instruction
+        _, runs["tn32"] = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
     finally:
         B.gcn_set_tunable("gemm_split", 1)
         B.gcn_set_tunable("fused_planes", 1)
         B.gcn_set_tunable("tn_beside", 1)
+        B.gcn_set_tunable("gemm_split_tn", 1)
     for name in ("H", "dW", "W", "dZ"):
         for x, y in zip(runs[(1, 1)][name], in_line[name]):
             np.testing.assert_array_equal(x, y)
     for key, gpu in runs.items():
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=0.25, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
-    a, b, c = runs[(1, 1)], runs[(0, 1)], runs[(1, 0)]
+    a, b, c, d = runs[(1, 1)], runs[(0, 1)], runs[(1, 0)], runs["tn32"]
     for name in ("H", "dW", "W"):
-        for x, y, z in zip(a[name], b[name], c[name]):
+        for x, y, z, u in zip(a[name], b[name], c[name], d[name]):
             np.testing.assert_array_equal(x, z)                                  # planes from the epilogue or not
-            scale = float(np.sqrt(np.mean(np.square(y.astype(np.float64))))) + 1e-30
-            assert float(np.max(np.abs(x.astype(np.float64) - y))) <= 1e-5 * scale * 8.0, name
+            for other in (y, u):
+                scale = float(np.sqrt(np.mean(np.square(other.astype(np.float64))))) + 1e-30
+                assert float(np.max(np.abs(x.astype(np.float64) - other))) <= 1e-5 * scale * 8.0, name
+    for x, u in zip(a["H"], d["H"]):
+        np.testing.assert_array_equal(x, u)                                      # (the forward pass is the same one)
     np.testing.assert_array_equal(a["logits"], c["logits"])
 
 
