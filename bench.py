@@ -361,10 +361,15 @@ def main() -> int:
 
         if parts:
             dom = max(parts, key=lambda k: parts[k]["ms_per_epoch"])
-            roofline = roofline_of(dom)
-            # the tile product and the gather of one aggregation run side by side on two streams: each one's time is
-            # taken while it shares the chip with the other, so the other one's position is given as well
+            # The tile product and the gather of one aggregation run side by side on two streams, each one's time
+            # taken while it shares the chip with the other (the two times differ by a tenth and which one is longer
+            # changes from run to run).  The pair is reported as one: the gather first (it moves nine tenths of the
+            # pair's bytes), the tile product under "runs_beside".
             kind, w = dom.split(".w")
+            if kind == "tiles" and "gather.w%s" % w in parts:
+                kind = "gather"
+            roofline = roofline_of("%s.w%s" % (kind, w))
+            roofline["longest_part_by_time"] = dom
             beside = {"tiles": "gather", "gather": "tiles"}.get(kind)
             if beside and "%s.w%s" % (beside, w) in parts:
                 roofline["runs_beside"] = roofline_of("%s.w%s" % (beside, w))
