@@ -49,9 +49,10 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  * shapes.  Results do not depend on any knob beyond rounding order.  Unknown names are stored and ignored.
  *   "cache_ax"          0 / 1 / 2    layer 1 as (A_hat X) W_1 from a cached A_hat X: never / when d_0 <= d_1 (default) /
  *                                    always; read by gcn_model_create
- *   "gemm_split"        1 / 0        float32 models: layer 1's feature transform on the bfloat16 matrix instruction
- *                                    from three-plane operands (default) / on the float32 instruction; read by
- *                                    gcn_model_workspace_bytes and gcn_model_create
+ *   "gemm_split"        0 / 1 / 2    float32 models: layer 1's feature transform on the bfloat16 matrix instruction
+ *                                    from three-plane operands: never (the float32 instruction) / when the input is
+ *                                    at least 256 wide (default) / always; read by gcn_model_workspace_bytes and
+ *                                    gcn_model_create
  *   "gemm_split_tn"     1 / 0        with "gemm_split" and layer 1 from the cached A_hat X: its weight gradient the
  *                                    same way, the vertices (the shared index) cut over workgroups (default) / on
  *                                    the float32 instruction; read by gcn_model_workspace_bytes and gcn_model_create

@@ -374,9 +374,15 @@ bool want_l1_cached(int32_t n_layers, const int32_t *dims) {
     return knob >= 2 || dims[0] <= dims[1];
 }
 
-// "gemm_split" knob (default 1): float32 models run layer 1's feature transform on the bfloat16 matrix instruction
-// with three-plane operands.
-bool want_l1_split(int dtype) { return dtype == GCN_F32 && tunable("gemm_split", 1) != 0; }
+// "gemm_split" knob: float32 models run layer 1's feature transform on the bfloat16 matrix instruction with
+// three-plane operands: 0 = never, 1 = when the input is at least 256 wide (default), 2 = always.  (The product
+// loads two blocks of 32 of the shared index ahead; over the four blocks of a 128-wide input that does not pay:
+// 128-128-40 on the 100,000-vertex Chung-Lu graph 2,086 against 2,136 epochs/s, 3,353 against 3,361 from the
+// cached A_hat X; the 602-wide Reddit shapes gain 2 to 8 %.)
+bool want_l1_split(int dtype, int d_in) {
+    const int64_t knob = tunable("gemm_split", 1);
+    return dtype == GCN_F32 && (knob >= 2 || (knob == 1 && d_in >= 256));
+}
 
 // Layer widths: 1..16 layers; the input may be up to 4096 wide; hidden and output widths are limited to what one
 // aggregation launch covers with a wave per row (64 lanes x 16 bytes): 256 columns in float32, 512 in bfloat16.
@@ -867,7 +873,7 @@ int gcn_model_workspace_bytes(const gcn_graph *g, int32_t n_layers, const int32_
     m.dtype = dtype;
     m.L = n_layers;
     m.l1_cached = want_l1_cached(n_layers, dims);
-    m.l1_split = want_l1_split(dtype);
+    m.l1_split = want_l1_split(dtype, dims[0]);
     for (int l = 0; l < n_layers; ++l)
         m.layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                  nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
@@ -915,7 +921,7 @@ int gcn_model_create(gcn_model **out, const gcn_graph *g, int32_t n_layers, cons
     m->p = dropout_p;
     m->seed = seed;
     m->l1_cached = want_l1_cached(n_layers, dims);
-    m->l1_split = want_l1_split(dtype);
+    m->l1_split = want_l1_split(dtype, dims[0]);
     for (int l = 0; l < n_layers; ++l)
         m->layers.push_back(Layer{dims[l], dims[l + 1], padded_width(dims[l]), padded_width(dims[l + 1]), nullptr,
                                   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});

@@ -435,11 +435,11 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
     assert B.gcn_graph_tile_info(g)["in_use"]
     runs = {}
     try:
-        for split, fused in ((1, 1), (0, 1), (1, 0)):
+        for split, fused in ((2, 1), (0, 1), (2, 0)):
             B.gcn_set_tunable("gemm_split", split)
             B.gcn_set_tunable("fused_planes", fused)
             _, runs[(split, fused)] = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
-        B.gcn_set_tunable("gemm_split", 1)
+        B.gcn_set_tunable("gemm_split", 2)
         B.gcn_set_tunable("fused_planes", 1)
         B.gcn_set_tunable("tn_beside", 0)       # the upper layer's weight gradient in line instead of beside
         _, in_line = H.gpu_epoch(B, g, wl, cache_ax=cache_ax, dropout_p=0.25, seed=5)
@@ -452,12 +452,12 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
         B.gcn_set_tunable("tn_beside", 1)
         B.gcn_set_tunable("gemm_split_tn", 1)
     for name in ("H", "dW", "W", "dZ"):
-        for x, y in zip(runs[(1, 1)][name], in_line[name]):
+        for x, y in zip(runs[(2, 1)][name], in_line[name]):
             np.testing.assert_array_equal(x, y)
     for key, gpu in runs.items():
         _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu, dropout_p=0.25, seed=5)
         H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
-    a, b, c, d = runs[(1, 1)], runs[(0, 1)], runs[(1, 0)], runs["tn32"]
+    a, b, c, d = runs[(2, 1)], runs[(0, 1)], runs[(2, 0)], runs["tn32"]
     for name in ("H", "dW", "W"):
         for x, y, z, u in zip(a[name], b[name], c[name], d[name]):
             np.testing.assert_array_equal(x, z)                                  # planes from the epilogue or not
