@@ -189,6 +189,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (scales rocprofv3 byte counters)")
+    ap.add_argument("--cache-ax", type=int, default=1, choices=[0, 1, 2],
+                    help="layer 1 as (A_hat X) W_1 from a cached A_hat X: 0 never, 1 the library's default (when the "
+                         "input is not wider than the first hidden layer), 2 always; the headline run is the default")
     ap.add_argument("--no-alt-mode", action="store_true",
                     help="skip the extra timed runs (cache_ax switch flipped; vertex ids shuffled)")
     ap.add_argument("--no-kernel-timing", action="store_true",
@@ -255,6 +258,7 @@ def main() -> int:
 
     # the library's default decides whether layer 1 runs from a cached A_hat X (it does when the input is
     # not wider than the first hidden layer); the headline number is that default
+    B.gcn_set_tunable("cache_ax", args.cache_ax)
     m = B.gcn_model_create(g, wl.dims, dtype=dtype)
     B.gcn_set_weights(m, wl.weights)
     warmup = 3
@@ -374,7 +378,7 @@ def main() -> int:
             if beside and "%s.w%s" % (beside, w) in parts:
                 roofline["runs_beside"] = roofline_of("%s.w%s" % (beside, w))
 
-    default_cached = wl.dims[0] <= wl.dims[1] and len(wl.dims) > 2
+    default_cached = len(wl.dims) > 2 and (args.cache_ax == 2 or (args.cache_ax == 1 and wl.dims[0] <= wl.dims[1]))
     other = None
     if not args.no_alt_mode and len(wl.dims) > 2:
         # the other setting of the same switch, timed the same way
@@ -382,7 +386,7 @@ def main() -> int:
         try:
             m2 = B.gcn_model_create(g, wl.dims, dtype=dtype)
         finally:
-            B.gcn_set_tunable("cache_ax", 1)
+            B.gcn_set_tunable("cache_ax", args.cache_ax)
         B.gcn_set_weights(m2, wl.weights)
         w2, e2 = timed_run(m2, wl.lr, args.steps, 0)
         other = {"layer1_from_cached_AX": not default_cached,
