@@ -8,9 +8,13 @@
 // 16 passes) needs 8 x 16 passes for.
 //
 // The product:  c [M x N] = a [M x K] b^T  (b has N rows of length K);  T = D^-1/2 (X W) has a = X [n x f] and
-// b = W^T [d x f].  (The weight gradient X^T G stays on the float32 instruction: in this form its right operand
-// G^T would be the long one, read again by every row tile of X^T, and packing it costs a pass per epoch; measured
-// slower.)
+// b = W^T [d x f].
+// The weight gradient of the same layer (dW = H^T G of the backward pass) is the same kernel's second form: a = the
+// packed transpose [f x n], the shared index is the vertices, and the right operand G [n x d] is not packed per call
+// (its transpose would be the long operand, read again by every row tile, and packing it costs a pass per epoch:
+// measured slower than the float32 instruction) but read as the float32 "units" that the dense products' epilogues
+// already write for the tile product (tiles.hip), and split into planes on the way into LDS.  The vertices are cut
+// over blockIdx.y, every cut writes its partial matrix, and the partial matrices are added in ascending order.
 // Both operands are stored "packed": in the order the instruction's lanes read them, in chunks of 32 operand rows x
 // 32 of the shared index, ordered [row tile][k-block].  Lane l of a 16-deep step holds row l % 32 and k-octet
 // l / 32.  A wave therefore loads a fragment as 64 consecutive 16-byte pieces, and walks through memory in one
