@@ -469,6 +469,30 @@ def test_split_product_and_epilogue_planes_against_the_plain_paths(B, oracle, ca
     np.testing.assert_array_equal(a["logits"], c["logits"])
 
 
+@pytest.mark.parametrize("n,f,hidden,classes", [(1999, 300, 16, 7), (2500, 256, 48, 5), (3001, 515, 200, 9),
+                                                 (700, 260, 128, 3), (4130, 1030, 72, 11)])
+def test_split_products_on_ragged_shapes(B, oracle, n, f, hidden, classes):
+    """Both forms of the three-plane product at sizes that end inside a tile everywhere: vertex counts that are no
+    multiple of 32 (the weight gradient's shared index, cut over workgroups: 3 cuts for 700 vertices, up to 17
+    for the others), input widths that are no multiple of 32 or 128 (its rows; the transform's shared index), hidden
+    widths of half a column tile, one and a half, two and a quarter, four, and six and a quarter (the last column
+    group of a workgroup partly or wholly past the end).  Layer 1 from the cached A_hat X, so that both forms run, then the
+    default form, where only the transform does."""
+    wl = workloads.tiny(n=n, classes=classes)
+    wl.dims = [f, hidden, classes]
+    wl.x = workloads._features(11, n, f)
+    wl.weights = workloads.glorot_weights(wl.dims, 12)
+    g = H.gpu_graph(B, wl)
+    B.gcn_set_tunable("gemm_split", 2)
+    try:
+        for mode in (2, 0):
+            _, gpu = H.gpu_epoch(B, g, wl, cache_ax=mode)
+            _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+            H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
+    finally:
+        B.gcn_set_tunable("gemm_split", 1)
+
+
 # ------------------------------------------------------------------ Adam
 def test_adam_update_kernel_matches_oracle(B, oracle):
     count = 100_003
