@@ -66,8 +66,11 @@ int gcn_timing_read(int32_t part, int32_t width, int64_t *launches, double *tota
  *   "tile_chunk"        0 / >= 8     tiles per run when a row block's tiles are cut: three quarters of the average per
  *                                    workgroup place (default) / that many; read by gcn_graph_create
  *   "spmm_overlap"      1 / 0        tile product beside the gather kernel (default) / before it
- *   "spmm_tiles_first"  0 / 1        which of the two goes to the graph's own stream: the tile product (default) /
- *                                    the gather
+ *   "spmm_tiles_first"  -1 / 0 / 1   which of the two is launched first, on the caller's stream (the other goes to the
+ *                                    graph's own): the gather when it runs the phased schedule, else the tile product
+ *                                    (default) / the gather / the tile product
+ *   "tile_run_max"      >= 16        tiles per work item of the tile product at most (default 128); read by
+ *                                    gcn_graph_create
  *   "fused_planes"      1 / 0        float32 models: the dense product that writes an aggregation's input also writes the
  *                                    tile product's operand planes (default) / a separate pass does
  *   "tn_beside"         1 / 0        backward pass: a layer's weight gradient on the graph's own stream beside the input

@@ -585,9 +585,9 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
         timing_close(t_all, st);
         return GCN_EINVAL;
     }
-    // Side by side: the tile product on the side stream, the gather over the residual entries on the caller's (knob
-    // "spmm_tiles_first": the other way round; measured the same on the benchmark partition, where both kernels
-    // slow each other down through the bytes they pull from the L2s: 254 us together against 195 + 98 us alone).
+    // Side by side: the tile product and the gather over the residual entries on two streams, the caller's and the
+    // graph's own (which one where: below).  Both kernels slow each other down through the bytes they pull from
+    // the L2s (the benchmark partition: 254 us together against 195 + 98 us alone).
     hipStream_t gather_stream = st;
     // The pass that lays the input out for the tile product.  float32: before the two parts are forked (beside the
     // gather it takes three times as long, and the tile product's is the longer of the two paths).  bfloat16: at the
@@ -602,7 +602,13 @@ int spmm_launch(const SpmmArgs &a, hipStream_t st) {
     if (a.tile_ptr && overlap) {
         rc = hip_status(hipEventRecord(a.ev_fork, st), "hipEventRecord");
         if (rc == GCN_OK) rc = hip_status(hipStreamWaitEvent(a.side, a.ev_fork, 0), "hipStreamWaitEvent");
-        if (rc == GCN_OK && tunable("spmm_tiles_first", 0) != 0) {
+        // Which of the two goes first into the chip (the caller's stream; the other follows on the side stream): the
+        // gather when it runs the phased schedule, whose grid must be resident at once (the benchmark partition:
+        // 943 against 817 epochs/s), the tile product otherwise, because it is the longer of the two (the full
+        // Reddit shape: 137.5 against 133.7 epochs/s).  Knob "spmm_tiles_first": -1 this rule, 0 / 1 fixed.
+        const int64_t first_knob = tunable("spmm_tiles_first", -1);
+        const bool tiles_first = first_knob < 0 ? a.phased_w <= 0 : first_knob != 0;
+        if (rc == GCN_OK && tiles_first) {
             if (!planes_first) rc = tiles_planes(a, st);
             if (rc == GCN_OK) rc = tiles_launch(a, a.tile_sums, a.cols, st);
             gather_stream = a.side;
