@@ -189,6 +189,7 @@ SpmmArgs spmm_args(const gcn_graph *g, const void *t, int t_dtype, int ld_t, voi
     a.prow = pb.prow;
 
     a.n = g->n;
+    a.spread = g->tiles_searched && g->nnz_dense * 16 < g->E;
     const gcn_graph::RowClasses &rc = masked ? g->bwd_rows : (tiles ? g->res_rows : g->rows);
     a.phased_w = rc.phased_w;
     a.phased_r = rc.phased_r;
@@ -561,6 +562,7 @@ int gcn_graph_create(gcn_graph **out, int64_t n, int64_t nnz_in, const int64_t *
         HIP_OR_FAIL(hipMemcpyAsync(&dense, g->tiles.totals, sizeof(dense), hipMemcpyDeviceToHost, st));
         HIP_OR_FAIL(hipStreamSynchronize(st));
         g->nnz_dense = (int64_t)dense;
+        g->tiles_searched = true;
         if (g->n_tiles > g->tiles.capacity) {   // cannot happen: every tile holds >= kTileMinEntriesFloor entries
             set_error("gcn_graph_create: dense tile count %lld exceeds capacity", (long long)g->n_tiles);
             delete g;

@@ -263,6 +263,8 @@ struct SpmmArgs {
     hipEvent_t ev_fork, ev_join;
     int finish_mode;     // set by spmm_launch, see SpmmFinish
     int planes_ready;    // tile_planes already holds this input (its producer wrote it through a PlaneSink)
+    int spread;          // the pattern was searched for dense tiles and has next to none: no community keeps its
+                         // vertices together, a row's entries are taken to be spread evenly over all columns
 };
 // Where the producer of an aggregation's float32 input also leaves it in the order the tile product reads it
 // (planes == nullptr: nowhere); n_ct blocks of 32 rows, per block and k-octet `ld` units of two 16-byte halves.

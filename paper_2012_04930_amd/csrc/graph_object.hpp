@@ -19,6 +19,7 @@ struct gcn_graph {
     gcn::PrepBuffers res{};
     int64_t n_tiles = 0, nnz_dense = 0;
     bool use_tiles = false;
+    bool tiles_searched = false;   // nnz_dense is a count, not a default
     // The pattern that the default form of the aggregation gathers over (the residual one with tiles in use, else
     // the whole one) without the columns of vertices outside the train mask: the rows of dLoss/dlogits are zero
     // there, so the last layer's backward aggregation gathers over this one.  Built when it drops enough entries.

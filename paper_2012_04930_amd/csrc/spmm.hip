@@ -483,8 +483,13 @@ constexpr int64_t kL2Bytes = 4 << 20;
 //   256-byte rows (bfloat16, width 128): 1.5 MB +14 %, 3.0 MB +4 %, 6.1 MB best
 //   192-byte rows (float32, width 48):   2.3 MB +6 %, 4.6 MB best, 9.1 MB +5 %
 // so rows of at least 512 bytes (a lane group of 32 or 64 lanes) get up to 5 MB, narrower ones up to 6.5 MB.
+// That partition keeps the vertices of a community together, so a phase's gathers fall on few of its rows.  Where
+// the entries are spread evenly over the columns (the same partition with its vertex ids scrambled) a phase's rows
+// must fit an L2 beside everything else: one column range of 1.5 MB per phase gave 554 epochs/s against 479 with two
+// and 415 with four.
 constexpr int64_t kPhaseBytesWide = 5 << 20;
 constexpr int64_t kPhaseBytesNarrow = (13 << 20) / 2;
+constexpr int64_t kPhaseBytesSpread = (13 << 20) / 8;
 
 template <typename TIn, typename TOut, int LPR, int U>
 bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
@@ -506,7 +511,8 @@ bool try_phased(const SpmmArgs &a, hipStream_t st, int *rc) {
     int64_t group = tunable("phased_group", 0);
     if (group <= 0)
         for (group = kColBlocks / 2;
-             group > 1 && group * block * row_bytes > (LPR >= 32 ? kPhaseBytesWide : kPhaseBytesNarrow);)
+             group > 1 && group * block * row_bytes >
+                              (a.spread ? kPhaseBytesSpread : (LPR >= 32 ? kPhaseBytesWide : kPhaseBytesNarrow));)
             group /= 2;
 #define GCN_PHASED(RR, GG)                                                                                           \
     k_spmm_phased<TIn, TOut, LPR, U, RR, GG><<<dim3(grid), dim3(kThreads), 0, st>>>(                                  \
