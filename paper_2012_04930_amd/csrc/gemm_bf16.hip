@@ -54,8 +54,15 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
     constexpr int BM = 32 * WM;
     constexpr int BN = 32 * TN * WN;
     static_assert(WM * WN == kThreads / 64, "four waves");
-    __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_LD];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_LD];
+    // LDS: the two operand tiles during the product; afterwards (nn, nt) the same bytes hold the output tile as
+    // bfloat16, rows C_LD apart, so that it leaves in 16-byte pieces along the rows
+    constexpr int C_LD = BN + 8;
+    constexpr int kStageBytes = (BM + BN) * LDS_LD * 2;
+    constexpr int kOutBytes = MODE == kTN ? 0 : BM * C_LD * 2;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kStageBytes > kOutBytes ? kStageBytes : kOutBytes];
+    bf16_t *const As = reinterpret_cast<bf16_t *>(smem);
+    bf16_t *const Bs = As + BM * LDS_LD;
+    bf16_t *const Cs = reinterpret_cast<bf16_t *>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
@@ -200,29 +207,67 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
         }
     }
 
-    const int64_t out_rows = (MODE == kTN) ? (int64_t)g.K : g.M;
+    if (MODE == kTN) {
+        float *cb = static_cast<float *>(g.c) + (int64_t)blockIdx.y * (int64_t)g.K * g.ldc;   // this split's partial matrix
 #pragma unroll
-    for (int t = 0; t < TN; ++t) {
-        const int col = n0 + (wn * TN + t) * 32 + l32;
+        for (int t = 0; t < TN; ++t) {
+            const int col = n0 + (wn * TN + t) * 32 + l32;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t row = m0 + wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            if (row < out_rows && col < g.ldc) {
-                float x = acc[t][v];
-                if (MODE == kTN) {
-                    float *cb = static_cast<float *>(g.c) + (int64_t)blockIdx.y * (int64_t)g.K * g.ldc;
-                    cb[row * g.ldc + col] = x;
-                } else {
-                    if (MODE == kNT) {
-                        const float gt = g.gate ? (float)g.gate[row * g.ldg + col] : 1.0f;
-                        x = gt > 0.0f ? x * g.scale : 0.0f;
-                    }
-                    if (g.rowscale) x *= g.rowscale[row];
-                    if (MODE == kNN) x = activate(x, g.act, row, col);
-                    static_cast<bf16_t *>(g.c)[row * g.ldc + col] = (bf16_t)x;
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = m0 + wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                if (row < (int64_t)g.K && col < g.ldc) cb[row * g.ldc + col] = acc[t][v];
             }
         }
+        return;
+    }
+
+    // nn, nt: the accumulator layout has a lane hold one column of 16 rows, i.e. 2-byte stores (and 2-byte gate loads)
+    // 2 x 64 bytes wide per instruction.  The tile goes through LDS instead: the gate tile comes in and the
+    // finished tile leaves in 16-byte pieces along the rows, a whole row of the tile per 4 to 16 lanes.
+    constexpr int ROW_VECS = BN / 8, TILE_VECS = BM * ROW_VECS, PER = TILE_VECS / kThreads;
+    static_assert(TILE_VECS % kThreads == 0, "whole passes");
+    __syncthreads();   // every wave has read its last fragments: the operand tiles may be overwritten
+    if (MODE == kNT && g.gate) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = tid + i * kThreads;
+            const int r = idx / ROW_VECS, c = (idx % ROW_VECS) * 8;
+            const int64_t row = m0 + r;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (row < g.M && n0 + c < g.ldc) v = *reinterpret_cast<const uint4 *>(g.gate + row * g.ldg + n0 + c);
+            *reinterpret_cast<uint4 *>(&Cs[r * C_LD + c]) = v;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const int cl = (wn * TN + t) * 32 + l32;
+        const int col = n0 + cl;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            const int64_t row = m0 + rl;
+            float x = acc[t][v];
+            if (MODE == kNT) {
+                const float gt = g.gate ? (float)Cs[rl * C_LD + cl] : 1.0f;   // (this thread alone touches the element)
+                x = gt > 0.0f ? x * g.scale : 0.0f;
+            }
+            if (row < g.M) {
+                if (g.rowscale) x *= g.rowscale[row];
+                if (MODE == kNN) x = activate(x, g.act, row, col);
+            }
+            Cs[rl * C_LD + cl] = (bf16_t)x;
+        }
+    }
+    __syncthreads();
+    bf16_t *const c = static_cast<bf16_t *>(g.c);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int idx = tid + i * kThreads;
+        const int r = idx / ROW_VECS, cc = (idx % ROW_VECS) * 8;
+        const int64_t row = m0 + r;
+        if (row < g.M && n0 + cc < g.ldc)
+            *reinterpret_cast<uint4 *>(c + row * g.ldc + n0 + cc) = *reinterpret_cast<const uint4 *>(&Cs[r * C_LD + cc]);
     }
 }
 
