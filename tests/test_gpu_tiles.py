@@ -28,7 +28,8 @@ def knobs(B):
         touched.append(name)
         B.gcn_set_tunable(name, value)
     yield set_
-    defaults = {"spmm_tiles": -1, "tile_min_entries": 64, "spmm_phased": -1, "spmm_overlap": 1, "spmm_masked": 1}
+    defaults = {"spmm_tiles": -1, "tile_min_entries": 64, "spmm_phased": -1, "spmm_overlap": 1, "spmm_masked": 1,
+                "spmm_tiles_first": -1}
     for name in touched:
         B.gcn_set_tunable(name, defaults[name])
 
@@ -181,6 +182,13 @@ def test_tile_product_beside_the_gather_kernel_or_before_it(B, oracle, knobs, wi
         H.assert_close(runs[0], ref, what="overlap %d, width %d" % (overlap, width))
         out[overlap] = runs[0]
     np.testing.assert_allclose(out[1], out[0], rtol=0, atol=4e-6 * np.abs(ref).max())
+    # side by side, either part launched first (on the caller's stream, the other on the graph's own): the same
+    # kernels on the same data, so the same bits
+    knobs("spmm_overlap", 1)
+    for first in (0, 1):
+        knobs("spmm_tiles_first", first)
+        for _ in range(2):
+            np.testing.assert_array_equal(B.gcn_aggregate(g, xd).cpu().numpy(), out[1])
 
 
 @pytest.mark.parametrize("tiles", [0, 1], ids=["whole_pattern", "residual_pattern"])
