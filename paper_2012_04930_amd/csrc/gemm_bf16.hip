@@ -25,6 +25,7 @@ constexpr int LDS_LD = BK + 8;   // bf16 elements per LDS row (80 bytes)
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes in flight (a plain vector: stays in registers)
 
 enum Mode { kNN = 0, kNT = 1, kTN = 2 };
 
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
     // ---- tn staging: units of 4 k-rows x 8 columns, A units first, then B units; at most one per thread
     constexpr int A_UNITS = (BK / 4) * (BM / 8), B_UNITS = (BK / 4) * (BN / 8);
     static_assert(MODE != kTN || A_UNITS + B_UNITS <= kThreads, "one transposing unit per thread");
-    uint4 ra[MODE == kTN ? 4 : A_PER], rb[MODE == kTN ? 1 : B_PER];
+    uint4 ra[MODE == kTN ? 4 : 1];                                    // tn: the four rows of a unit
+    u32x4 va[MODE == kTN ? 1 : A_PER], vb[MODE == kTN ? 1 : B_PER];   // nn, nt
 
     auto fetch = [&](int64_t k0) {
         if (MODE == kTN) {
@@ -122,26 +124,26 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
 #pragma unroll
             for (int i = 0; i < A_PER; ++i) {
                 const int idx = tid + i * kThreads;
-                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                u32x4 v = {0u, 0u, 0u, 0u};
                 if (idx < A_VECS) {
                     const int m = idx / (BK / 8), kq = idx % (BK / 8);
                     const int64_t row = m0 + m;
                     const int64_t k = k0 + kq * 8;
-                    if (row < g.M && k < kend) v = *reinterpret_cast<const uint4 *>(g.a + row * g.lda + k);
+                    if (row < g.M && k < kend) v = *reinterpret_cast<const u32x4 *>(g.a + row * g.lda + k);
                 }
-                ra[i] = v;
+                va[i] = v;
             }
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
                 const int idx = tid + i * kThreads;
-                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                u32x4 v = {0u, 0u, 0u, 0u};
                 if (idx < B_VECS) {
                     const int nn = idx / (BK / 8), kq = idx % (BK / 8);
                     const int row = n0 + nn;
                     const int64_t k = k0 + kq * 8;
-                    if (row < g.N && k < kend) v = *reinterpret_cast<const uint4 *>(g.b + (int64_t)row * g.ldb + k);
+                    if (row < g.N && k < kend) v = *reinterpret_cast<const u32x4 *>(g.b + (int64_t)row * g.ldb + k);
                 }
-                rb[i] = v;
+                vb[i] = v;
             }
         }
     };
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
                 const int idx = tid + i * kThreads;
                 if (idx < A_VECS) {
                     const int m = idx / (BK / 8), kq = idx % (BK / 8);
-                    *reinterpret_cast<uint4 *>(&As[m * LDS_LD + kq * 8]) = ra[i];
+                    *reinterpret_cast<u32x4 *>(&As[m * LDS_LD + kq * 8]) = va[i];
                 }
             }
 #pragma unroll
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
                 const int idx = tid + i * kThreads;
                 if (idx < B_VECS) {
                     const int nn = idx / (BK / 8), kq = idx % (BK / 8);
-                    *reinterpret_cast<uint4 *>(&Bs[nn * LDS_LD + kq * 8]) = rb[i];
+                    *reinterpret_cast<u32x4 *>(&Bs[nn * LDS_LD + kq * 8]) = vb[i];
                 }
             }
         }
@@ -202,7 +204,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
             for (int t = 0; t < TN; ++t) {
                 const bf16x8 bfr =
                     *reinterpret_cast<const bf16x8 *>(&Bs[((wn * TN + t) * 32 + l32) * LDS_LD + ks * 16 + h * 8]);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);
+                // nn, nt: the operands change places, so the instruction forms the transposed tile and a lane ends up
+                // with four consecutive columns of ONE output row per register quad (see the epilogue below)
+                acc[t] = MODE == kTN ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0)
+                                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af, acc[t], 0, 0, 0);
             }
         }
     }
@@ -221,9 +226,13 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
         return;
     }
 
-    // nn, nt: the accumulator layout has a lane hold one column of 16 rows, i.e. 2-byte stores (and 2-byte gate loads)
-    // 2 x 64 bytes wide per instruction.  The tile goes through LDS instead: the gate tile comes in and the
-    // finished tile leaves in 16-byte pieces along the rows, a whole row of the tile per 4 to 16 lanes.
+    // nn, nt.  With the operands in their usual places a lane would hold one column of 16 rows: 2-byte stores and
+    // gate loads, one row scale and one float -> bfloat16 conversion per element, and the kernel is bound by
+    // those vector instructions, not by the matrix pipes or memory.  With the operands swapped a lane holds, of
+    // output row wm * 32 + l32, the columns 8 q + 4 h + 0..3 of each 32-column tile in registers 4 q .. 4 q + 3: one
+    // row scale per lane, and four values at a time to gate, convert and store as 8 bytes.  The tile goes through
+    // LDS (the bytes the operand tiles used): the gate tile comes in and the finished tile leaves in 16-byte pieces
+    // along the rows, a whole row of the tile per 4 to 16 lanes.
     constexpr int ROW_VECS = BN / 8, TILE_VECS = BM * ROW_VECS, PER = TILE_VECS / kThreads;
     static_assert(TILE_VECS % kThreads == 0, "whole passes");
     __syncthreads();   // every wave has read its last fragments: the operand tiles may be overwritten
@@ -239,24 +248,44 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(Args g) {
         }
         __syncthreads();
     }
+    {
+        const int rl = wm * 32 + l32;
+        const int64_t row = m0 + rl;
+        const bool live = row < g.M;
+        const float rs = (live && g.rowscale) ? g.rowscale[row] : 1.0f;
+        const bool relu = g.act.kind == kActRelu, drop = relu && g.act.drop_threshold != 0u;
 #pragma unroll
-    for (int t = 0; t < TN; ++t) {
-        const int cl = (wn * TN + t) * 32 + l32;
-        const int col = n0 + cl;
+        for (int t = 0; t < TN; ++t) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rl = wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            const int64_t row = m0 + rl;
-            float x = acc[t][v];
-            if (MODE == kNT) {
-                const float gt = g.gate ? (float)Cs[rl * C_LD + cl] : 1.0f;   // (this thread alone touches the element)
-                x = gt > 0.0f ? x * g.scale : 0.0f;
+            for (int q = 0; q < 4; ++q) {
+                const int cl = (wn * TN + t) * 32 + 8 * q + 4 * h;
+                bf16_t *const spot = &Cs[rl * C_LD + cl];   // (this thread alone touches these four elements)
+                float x[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[i] = acc[t][4 * q + i];
+                if (MODE == kNT) {
+                    if (g.gate) {
+                        const uint2 gw = *reinterpret_cast<const uint2 *>(spot);
+                        // a bfloat16 is positive when it is neither zero nor negative: sign clear, rest non-zero
+                        const uint32_t e[4] = {gw.x & 0xffffu, gw.x >> 16, gw.y & 0xffffu, gw.y >> 16};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float gt = __uint_as_float(e[i] << 16);
+                            x[i] = gt > 0.0f ? x[i] * g.scale : 0.0f;
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) x[i] *= g.scale;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[i] *= rs;
+                    if (MODE == kNN && relu) x[i] = x[i] > 0.0f ? x[i] : 0.0f;
+                    if (MODE == kNN && drop && live) x[i] = activate(x[i], g.act, row, n0 + cl + i);   // (keeps or zeroes)
+                }
+                store_elems<4>(spot, x);   // 8 bytes
             }
-            if (row < g.M) {
-                if (g.rowscale) x *= g.rowscale[row];
-                if (MODE == kNN) x = activate(x, g.act, row, col);
-            }
-            Cs[rl * C_LD + cl] = (bf16_t)x;
         }
     }
     __syncthreads();
