@@ -104,7 +104,8 @@ int gcn_graph_info(const gcn_graph *g, int64_t *n, int64_t *nnz, int64_t *n_trai
  * (values below 2^-110 in magnitude lose their last bits).  bfloat16 rows take one pass.  A non-finite value in
  * a row of the aggregated matrix reaches, through 0 x inf, all 128 rows of the tiles that cover it.
  * Streams: with the split in use the tile product (a pass that splits and reorders the input, then the product)
- * runs on a stream of default priority that the graph owns, beside the gather kernel on the caller's stream;
+ * runs beside the gather kernel, one of the two on the caller's stream and the other on a stream of default
+ * priority that the graph owns (the gather on the caller's where it runs the phased schedule, else the tile product);
  * fork and join are done with events, so the caller's stream order is kept, and a last launch adds the two
  * parts.  Tunable "spmm_overlap": 1 = this (default), 0 = one launch after the other on the caller's stream
  * (float32 storage; bfloat16 matrices are then gathered whole).  Because that stream and its events belong to the graph, calls that aggregate over one graph
