@@ -586,6 +586,29 @@ def test_phased_schedule_with_every_number_of_column_ranges_per_phase(B, oracle,
         B.gcn_set_tunable("phased_group", 0)
 
 
+def test_partition_with_scrambled_vertex_ids(B, oracle):
+    """The same kind of partition with its vertex ids scrambled: the search for dense tiles finds next to none, the
+    aggregation is one gather over the whole pattern, and the phased schedule (forced here: the graph is small)
+    sizes its phases for entries spread over all columns.  Aggregation at two widths and a whole epoch against the
+    oracle."""
+    wl = workloads.reddit_partition(scale=0.2, avg_degree=100.0, shuffle_ids=True)   # (1 % of all pairs, as at full size)
+    g = H.gpu_graph(B, wl)
+    info = B.gcn_graph_tile_info(g)
+    assert not info["in_use"] and info["nnz_dense"] * 16 < B.gcn_graph_info(g)["nnz"]
+    og = oracle.canonicalise(wl.n, wl.rowptr, wl.col)
+    B.gcn_set_tunable("spmm_phased", 1)
+    try:
+        for width in (41, 128):
+            x = rng.normal_f32(width, 8, wl.n * width).reshape(wl.n, width)
+            got = B.gcn_aggregate(g, torch.from_numpy(x).cuda()).cpu().numpy()
+            H.assert_close(got, oracle.aggregate(og, x), rtol=H.RTOL_F32, what="scrambled ids, width %d" % width)
+        _, gpu = H.gpu_epoch(B, g, wl)
+    finally:
+        B.gcn_set_tunable("spmm_phased", -1)
+    _, tr, new = H.oracle_epoch(oracle, wl, gpu=gpu)
+    H.compare_epoch(oracle, wl, gpu, tr, new, rtol=H.RTOL_F32)
+
+
 def test_workgroups_are_dealt_round_robin_over_the_xcds(B):
     """The aggregation kernels give the workgroups b with equal b mod 8 one contiguous range of rows and count on them
     sharing an XCD (and its L2).  That rests on this dispatch order: workgroup b runs on XCD (b + s) mod 8, with a
